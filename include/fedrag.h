@@ -1,0 +1,140 @@
+/*
+ * fedrag.h - C ABI of the MI355X (gfx950) hot path of FedRAG's Scrambled Distributed Attention:
+ * one collaborating node's share of the protocol of Section 4 of the paper.
+ *
+ * General rules for every call
+ * ----------------------------
+ * - Every data pointer is DEVICE memory owned by the caller, 16-byte aligned, dense row-major.
+ *   The library never allocates, frees or keeps a pointer after the call returns.
+ * - Tensors are laid out [batch, heads, tokens, d_head] ("[B,H,L,d]").  Query head h uses KV head
+ *   h / (n_q_heads / n_kv_heads); scrambling matrices are per KV head, [n_kv_heads, d, d], row-major,
+ *   and multiply ROW vectors from the right (x . Phi), the paper's convention (Section 2.1, footnote).
+ * - `dtype` is the storage type of Q/K/V and of the scrambling matrices applied to them
+ *   (FEDRAG_F32, FEDRAG_BF16 or FEDRAG_F16).  Partial outputs, log-sum-exps, merged and unscrambled
+ *   outputs, and Phi_V^{-1}, are always fp32.
+ * - Token permutations are int32 GATHER index arrays: out row j <- in row perm[j].  Being a
+ *   bijection on [0, L) is the caller's responsibility and is not checked on the hot path.
+ * - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only enqueue work;
+ *   they never synchronise with the host and never copy between host and device.
+ * - All argument checks happen on the host BEFORE any HIP call; on any error nothing is enqueued and
+ *   no output is written.  Errors are return codes only.  FEDRAG_ERR_DEVICE reports a failed launch.
+ * - Supported: d_head in {64, 128}; n_q_heads % n_kv_heads == 0; token counts >= 0 (zero is legal).
+ * - The library draws no randomness: keys (Phi's, permutations) come from the key holders
+ *   (Inquirer and Context Owner negotiate them per request, Section 5.1 / Section 6).
+ *
+ * Roles (Section 5.1), documented, not enforced: fedrag_scramble_kv is the Context Owner's call;
+ * fedrag_scramble_q and fedrag_unscramble are the Inquirer's; fedrag_partial_attn is the Compute
+ * Node's and takes no key material; fedrag_lse_merge may run on either side.
+ */
+#ifndef FEDRAG_H
+#define FEDRAG_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    FEDRAG_OK = 0,
+    FEDRAG_ERR_NULL = 1,        /* a required pointer is NULL */
+    FEDRAG_ERR_SHAPE = 2,       /* negative size, heads not divisible, n_perm not in {1,B}, n_shards < 1 ... */
+    FEDRAG_ERR_UNSUPPORTED = 3, /* d_head or dtype not supported */
+    FEDRAG_ERR_WORKSPACE = 4,   /* workspace NULL or smaller than fedrag_partial_attn_workspace_bytes() */
+    FEDRAG_ERR_ALIAS = 5,       /* an output overlaps an input of an out-of-place call, or misaligned pointer */
+    FEDRAG_ERR_DEVICE = 6       /* the HIP runtime refused a launch */
+} fedrag_status;
+
+typedef enum { FEDRAG_F32 = 0, FEDRAG_BF16 = 1, FEDRAG_F16 = 2 } fedrag_dtype;
+
+typedef struct {
+    int32_t batch;      /* B: independent sequences */
+    int32_t n_q_heads;  /* Hq */
+    int32_t n_kv_heads; /* Hkv, divides Hq */
+    int32_t d_head;     /* d: 64 or 128 */
+    int32_t dtype;      /* fedrag_dtype of Q/K/V and of phi_q / phi_k / phi_v */
+} fedrag_shape;
+
+/*
+ * Enc for the Context Owner's operands (Section 4.2, "Scrambled Attention Protocol", step 1;
+ * token permutation paragraph):   K' = P_KV K Phi_KQ^{-T},   V' = P_KV V Phi_V,  i.e.
+ *     K_out[b,g,j,:] = K[b,g,perm_kv[p,j],:] . phi_k[g]      V_out likewise with phi_v[g]
+ * K, V, K_out, V_out : [B, Hkv, L_kv, d] in shape->dtype.  Out of place: outputs must not overlap
+ *                      inputs (FEDRAG_ERR_ALIAS).
+ * phi_k              : [Hkv, d, d] = Phi_KQ^{-T} (the caller inverts and transposes); phi_v = Phi_V.
+ * perm_kv            : [n_perm, L_kv] int32 gather indices, n_perm == 1 (shared by every sequence) or
+ *                      n_perm == B; NULL = identity.  One permutation serves all KV heads and both K and V.
+ * Products are accumulated in fp32 and rounded once (RNE) to shape->dtype.
+ */
+fedrag_status fedrag_scramble_kv(const fedrag_shape* shape, int64_t L_kv,
+                                 const void* K, const void* V,
+                                 const void* phi_k, const void* phi_v,
+                                 const int32_t* perm_kv, int32_t n_perm,
+                                 void* K_out, void* V_out, void* stream);
+
+/*
+ * Enc for the Inquirer's operand (same passage):   Q' = P_Q Q Phi_KQ,
+ *     Q_out[b,h,i,:] = Q[b,h,perm_q[i],:] . phi_q[h / G]
+ * Q, Q_out : [B, Hq, L_q, d] in shape->dtype, out of place.  phi_q : [Hkv, d, d] = Phi_KQ.
+ * perm_q   : [L_q] int32 gather indices or NULL (identity; decode has L_q == 1).
+ */
+fedrag_status fedrag_scramble_q(const fedrag_shape* shape, int64_t L_q, const void* Q,
+                                const void* phi_q, const int32_t* perm_q,
+                                void* Q_out, void* stream);
+
+/*
+ * The Compute Node's work on one KV shard (Section 4.1, "Per-Node Local Computation"):
+ *     O_part[b,h,i,:] = softmax_t( <Qs[b,h,i], Ks[b,g,t]> * softmax_scale ) . Vs[b,g,:,:]
+ *     lse[b,h,i]      = ln sum_t exp( <Qs[b,h,i], Ks[b,g,t]> * softmax_scale )  ( = ln [w_i]_l )
+ * No mask: every query row sees every key of the shard.  The normalisation factor is carried as its
+ * natural logarithm so that outlier logits cannot overflow; softmax_scale is applied in fp32 to the
+ * accumulated dot product (pass 1/sqrt(d)).
+ * Qs : [B,Hq,L_q,d], Ks/Vs : [B,Hkv,L_kv,d] in shape->dtype.  O_part : fp32 [B,Hq,L_q,d], lse : fp32 [B,Hq,L_q].
+ * L_kv == 0 gives O_part = 0 and lse = -inf.
+ * workspace : device scratch of at least fedrag_partial_attn_workspace_bytes(shape, L_q, L_kv) bytes
+ *             (intra-shard KV splits land there and are merged with the Section 4.1 aggregation);
+ *             contents are undefined afterwards.  May be NULL only when that size is 0.
+ */
+fedrag_status fedrag_partial_attn(const fedrag_shape* shape, int64_t L_q, int64_t L_kv,
+                                  const void* Qs, const void* Ks, const void* Vs, float softmax_scale,
+                                  float* O_part, float* lse,
+                                  void* workspace, size_t workspace_bytes, void* stream);
+
+size_t fedrag_partial_attn_workspace_bytes(const fedrag_shape* shape, int64_t L_q, int64_t L_kv);
+
+/*
+ * Global aggregation (Section 4.1): sum_i w_i (.) O_i / sum_i w_i with w_i = exp(lse_i), evaluated as
+ *     M = max_i lse_i, a_i = exp(lse_i - M), O = sum a_i O_i / sum a_i, lse = M + ln sum a_i.
+ * O_parts : fp32 [S,B,Hq,L_q,d], lses : fp32 [S,B,Hq,L_q] -> O_out fp32 [B,Hq,L_q,d], lse_out fp32 [B,Hq,L_q].
+ * A shard whose lse is -inf has weight 0; if all are -inf the row is O = 0, lse = -inf.  Never NaN for
+ * finite O_parts.  Out of place: outputs must not overlap inputs.  shape->dtype is ignored.
+ */
+fedrag_status fedrag_lse_merge(const fedrag_shape* shape, int64_t L_q, int32_t n_shards,
+                               const float* O_parts, const float* lses,
+                               float* O_out, float* lse_out, void* stream);
+
+/*
+ * Dec (Section 4.2, protocol step 3):  P_Q^{-1} (.) Phi_V^{-1},
+ *     O_out[b,h,perm_q[i],:] = O_scr[b,h,i,:] . phi_v_inv[h / G]
+ * O_scr, O_out : fp32 [B,Hq,L_q,d], out of place.  phi_v_inv : fp32 [Hkv,d,d].
+ * perm_q : the SAME gather array given to fedrag_scramble_q (the inverse is applied as a scatter), or NULL.
+ * fp32 inputs are multiplied in fp32 (they are not narrowed to the storage type).  shape->dtype is ignored.
+ */
+fedrag_status fedrag_unscramble(const fedrag_shape* shape, int64_t L_q, const float* O_scr,
+                                const float* phi_v_inv, const int32_t* perm_q,
+                                float* O_out, void* stream);
+
+/* inv_out[perm[j]] = j for j in [0, L): the gather array that undoes `perm`.  Device pointers. */
+fedrag_status fedrag_invert_perm(const int32_t* perm, int64_t L, int32_t* inv_out, void* stream);
+
+/* Static, human-readable name of a status code (host pointer, never NULL). */
+const char* fedrag_status_string(fedrag_status status);
+
+/* Library version, major * 10000 + minor * 100 + patch. */
+int fedrag_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FEDRAG_H */

@@ -1,0 +1,191 @@
+"""ctypes binding of the C-ABI library (include/fedrag.h), one Python function per entry point.
+
+Argument marshalling only: tensors are torch CUDA tensors used as device memory, the stream is torch's
+current HIP stream.  Every step of the path runs in the library's kernels; there is no fallback: if the
+library has not been built, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch  # noqa: F401  (imported before the library so that both share one HIP runtime)
+
+from . import build as _build
+
+OK, ERR_NULL, ERR_SHAPE, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_ALIAS, ERR_DEVICE = range(7)
+F32, BF16, F16 = 0, 1, 2
+_DTYPES = {torch.float32: F32, torch.bfloat16: BF16, torch.float16: F16}
+
+EXPORTS = ("fedrag_scramble_kv", "fedrag_scramble_q", "fedrag_partial_attn",
+           "fedrag_partial_attn_workspace_bytes", "fedrag_lse_merge", "fedrag_unscramble",
+           "fedrag_invert_perm", "fedrag_status_string", "fedrag_version")
+
+
+class Shape(ctypes.Structure):
+    _fields_ = [("batch", ctypes.c_int32), ("n_q_heads", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32),
+                ("d_head", ctypes.c_int32), ("dtype", ctypes.c_int32)]
+
+
+class FedragError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} (status {status})")
+
+
+_lib = None
+
+
+def lib_path() -> str:
+    return _build.LIB_PATH
+
+
+def load() -> ctypes.CDLL:
+    """Load libfedrag.so (built in-tree by paper_2605_25716_amd.build).  Raises if it is missing."""
+    global _lib
+    if _lib is None:
+        path = lib_path()
+        if not os.path.exists(path):
+            raise FileNotFoundError(
+                f"{path} not found: build it first (python -m paper_2605_25716_amd.build); "
+                "this package has no fallback path")
+        lib = ctypes.CDLL(path)
+        vp, i64, i32, f32p = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_void_p
+        sp = ctypes.POINTER(Shape)
+        lib.fedrag_scramble_kv.argtypes = [sp, i64, vp, vp, vp, vp, vp, i32, vp, vp, vp]
+        lib.fedrag_scramble_q.argtypes = [sp, i64, vp, vp, vp, vp, vp]
+        lib.fedrag_partial_attn.argtypes = [sp, i64, i64, vp, vp, vp, ctypes.c_float, f32p, f32p, vp,
+                                            ctypes.c_size_t, vp]
+        lib.fedrag_partial_attn_workspace_bytes.argtypes = [sp, i64, i64]
+        lib.fedrag_partial_attn_workspace_bytes.restype = ctypes.c_size_t
+        lib.fedrag_lse_merge.argtypes = [sp, i64, i32, f32p, f32p, f32p, f32p, vp]
+        lib.fedrag_unscramble.argtypes = [sp, i64, f32p, f32p, vp, f32p, vp]
+        lib.fedrag_invert_perm.argtypes = [vp, i64, vp, vp]
+        lib.fedrag_status_string.argtypes = [ctypes.c_int]
+        lib.fedrag_status_string.restype = ctypes.c_char_p
+        lib.fedrag_version.restype = ctypes.c_int
+        for name in ("fedrag_scramble_kv", "fedrag_scramble_q", "fedrag_partial_attn", "fedrag_lse_merge",
+                     "fedrag_unscramble", "fedrag_invert_perm"):
+            getattr(lib, name).restype = ctypes.c_int
+        _lib = lib
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return load().fedrag_status_string(int(status)).decode()
+
+
+def version() -> int:
+    return int(load().fedrag_version())
+
+
+def _check(status: int, where: str) -> None:
+    if status != OK:
+        raise FedragError(status, where)
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError("the library works on device memory: pass CUDA tensors")
+    if not t.is_contiguous():
+        raise ValueError("tensors must be dense row-major (contiguous)")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def make_shape(batch: int, n_q_heads: int, n_kv_heads: int, d_head: int, dtype) -> Shape:
+    code = _DTYPES[dtype] if isinstance(dtype, torch.dtype) else int(dtype)
+    return Shape(batch, n_q_heads, n_kv_heads, d_head, code)
+
+
+def _shape_of(q_like: torch.Tensor, n_kv_heads: int, dtype=None) -> Shape:
+    B, Hq, _, d = q_like.shape
+    return make_shape(B, Hq, n_kv_heads, d, q_like.dtype if dtype is None else dtype)
+
+
+# ----------------------------------------------------------------------------------------------- entry points
+def fedrag_scramble_kv(K, V, phi_k, phi_v, perm_kv=None, n_q_heads: Optional[int] = None,
+                       K_out=None, V_out=None):
+    """K' = P_KV K Phi_KQ^{-T}, V' = P_KV V Phi_V for one shard.  K, V [B,Hkv,L,d]; perm_kv [n_perm,L] or [L]."""
+    B, Hkv, L, d = K.shape
+    shape = make_shape(B, n_q_heads or Hkv, Hkv, d, K.dtype)
+    K_out = torch.empty_like(K) if K_out is None else K_out
+    V_out = torch.empty_like(V) if V_out is None else V_out
+    n_perm = 0
+    if perm_kv is not None:
+        n_perm = 1 if perm_kv.dim() == 1 else perm_kv.shape[0]
+    st = load().fedrag_scramble_kv(ctypes.byref(shape), L, _ptr(K), _ptr(V), _ptr(phi_k), _ptr(phi_v),
+                                   _ptr(perm_kv), n_perm, _ptr(K_out), _ptr(V_out), _stream())
+    _check(st, "fedrag_scramble_kv")
+    return K_out, V_out
+
+
+def fedrag_scramble_q(Q, phi_q, perm_q=None, Q_out=None):
+    """Q' = P_Q Q Phi_KQ.  Q [B,Hq,Lq,d]; phi_q [Hkv,d,d]."""
+    B, Hq, Lq, d = Q.shape
+    shape = make_shape(B, Hq, phi_q.shape[0], d, Q.dtype)
+    Q_out = torch.empty_like(Q) if Q_out is None else Q_out
+    st = load().fedrag_scramble_q(ctypes.byref(shape), Lq, _ptr(Q), _ptr(phi_q), _ptr(perm_q), _ptr(Q_out), _stream())
+    _check(st, "fedrag_scramble_q")
+    return Q_out
+
+
+def fedrag_partial_attn_workspace_bytes(batch, n_q_heads, n_kv_heads, d_head, dtype, L_q, L_kv) -> int:
+    shape = make_shape(batch, n_q_heads, n_kv_heads, d_head, dtype)
+    return int(load().fedrag_partial_attn_workspace_bytes(ctypes.byref(shape), L_q, L_kv))
+
+
+def fedrag_partial_attn(Qs, Ks, Vs, softmax_scale: Optional[float] = None, O_part=None, lse=None, workspace=None):
+    """One shard's (O_i, lse_i).  Qs [B,Hq,Lq,d], Ks/Vs [B,Hkv,L,d] -> fp32 [B,Hq,Lq,d], fp32 [B,Hq,Lq]."""
+    B, Hq, Lq, d = Qs.shape
+    Hkv, L = Ks.shape[1], Ks.shape[2]
+    shape = make_shape(B, Hq, Hkv, d, Qs.dtype)
+    if softmax_scale is None:
+        softmax_scale = float(d) ** -0.5
+    O_part = torch.empty((B, Hq, Lq, d), dtype=torch.float32, device=Qs.device) if O_part is None else O_part
+    lse = torch.empty((B, Hq, Lq), dtype=torch.float32, device=Qs.device) if lse is None else lse
+    need = int(load().fedrag_partial_attn_workspace_bytes(ctypes.byref(shape), Lq, L))
+    if workspace is None and need > 0:
+        workspace = torch.empty(need, dtype=torch.uint8, device=Qs.device)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    st = load().fedrag_partial_attn(ctypes.byref(shape), Lq, L, _ptr(Qs), _ptr(Ks) if L > 0 else None,
+                                    _ptr(Vs) if L > 0 else None, ctypes.c_float(softmax_scale), _ptr(O_part),
+                                    _ptr(lse), _ptr(workspace), ws_bytes, _stream())
+    _check(st, "fedrag_partial_attn")
+    return O_part, lse
+
+
+def fedrag_lse_merge(O_parts, lses, n_kv_heads: Optional[int] = None, O_out=None, lse_out=None):
+    """Aggregation over shards.  O_parts fp32 [S,B,Hq,Lq,d], lses fp32 [S,B,Hq,Lq]."""
+    S, B, Hq, Lq, d = O_parts.shape
+    shape = make_shape(B, Hq, n_kv_heads or Hq, d, F32)
+    O_out = torch.empty((B, Hq, Lq, d), dtype=torch.float32, device=O_parts.device) if O_out is None else O_out
+    lse_out = torch.empty((B, Hq, Lq), dtype=torch.float32, device=O_parts.device) if lse_out is None else lse_out
+    st = load().fedrag_lse_merge(ctypes.byref(shape), Lq, S, _ptr(O_parts), _ptr(lses), _ptr(O_out), _ptr(lse_out),
+                                 _stream())
+    _check(st, "fedrag_lse_merge")
+    return O_out, lse_out
+
+
+def fedrag_unscramble(O_scr, phi_v_inv, perm_q=None, O_out=None):
+    """Dec: out[b,h,perm_q[i]] = O_scr[b,h,i] @ phi_v_inv[h // G].  O_scr fp32 [B,Hq,Lq,d]; phi_v_inv fp32 [Hkv,d,d]."""
+    B, Hq, Lq, d = O_scr.shape
+    shape = make_shape(B, Hq, phi_v_inv.shape[0], d, F32)
+    O_out = torch.empty_like(O_scr) if O_out is None else O_out
+    st = load().fedrag_unscramble(ctypes.byref(shape), Lq, _ptr(O_scr), _ptr(phi_v_inv), _ptr(perm_q), _ptr(O_out),
+                                  _stream())
+    _check(st, "fedrag_unscramble")
+    return O_out
+
+
+def fedrag_invert_perm(perm, inv_out=None):
+    inv_out = torch.empty_like(perm) if inv_out is None else inv_out
+    st = load().fedrag_invert_perm(_ptr(perm), perm.numel(), _ptr(inv_out), _stream())
+    _check(st, "fedrag_invert_perm")
+    return inv_out

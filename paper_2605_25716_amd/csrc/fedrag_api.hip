@@ -1,0 +1,214 @@
+// C-ABI entry points (include/fedrag.h): host-side argument validation, then kernel launches.
+// Every check below runs before the first HIP call, so the error paths work on a machine without a GPU.
+#include "fedrag_host.h"
+
+using namespace fedrag;
+
+namespace {
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+size_t elem_size(int dtype) { return dtype == FEDRAG_F32 ? 4 : 2; }
+
+bool overlaps(const void* a, size_t na, const void* b, size_t nb) {
+    if (!a || !b || na == 0 || nb == 0) return false;
+    const uintptr_t a0 = reinterpret_cast<uintptr_t>(a), b0 = reinterpret_cast<uintptr_t>(b);
+    return a0 < b0 + nb && b0 < a0 + na;
+}
+
+fedrag_status check_shape(const fedrag_shape* s, bool need_dtype) {
+    if (!s) return FEDRAG_ERR_NULL;
+    if (s->batch < 0 || s->n_q_heads <= 0 || s->n_kv_heads <= 0) return FEDRAG_ERR_SHAPE;
+    if (s->n_q_heads % s->n_kv_heads != 0) return FEDRAG_ERR_SHAPE;
+    if (s->d_head != 64 && s->d_head != 128) return FEDRAG_ERR_UNSUPPORTED;
+    if (need_dtype && s->dtype != FEDRAG_F32 && s->dtype != FEDRAG_BF16 && s->dtype != FEDRAG_F16)
+        return FEDRAG_ERR_UNSUPPORTED;
+    return FEDRAG_OK;
+}
+
+// number of elements of a [B, H, L, d] tensor; false on int64 overflow
+bool tensor_elems(int64_t B, int64_t H, int64_t L, int64_t d, int64_t* out) {
+    int64_t n = 1;
+    const int64_t f[4] = {B, H, L, d};
+    for (int i = 0; i < 4; ++i) {
+        if (f[i] < 0) return false;
+        if (f[i] != 0 && n > INT64_MAX / 8 / f[i]) return false;
+        n *= f[i];
+    }
+    *out = n;
+    return true;
+}
+
+fedrag_status dev(hipError_t e) { return e == hipSuccess ? FEDRAG_OK : FEDRAG_ERR_DEVICE; }
+
+}  // namespace
+
+extern "C" {
+
+fedrag_status fedrag_scramble_kv(const fedrag_shape* shape, int64_t L_kv, const void* K, const void* V,
+                                 const void* phi_k, const void* phi_v, const int32_t* perm_kv, int32_t n_perm,
+                                 void* K_out, void* V_out, void* stream) {
+    fedrag_status st = check_shape(shape, true);
+    if (st != FEDRAG_OK) return st;
+    if (L_kv < 0 || L_kv > INT32_MAX) return FEDRAG_ERR_SHAPE;  // gather indices are int32
+    if (!K || !V || !phi_k || !phi_v || !K_out || !V_out) return FEDRAG_ERR_NULL;
+    if (perm_kv && n_perm != 1 && n_perm != shape->batch) return FEDRAG_ERR_SHAPE;
+    int64_t n;
+    if (!tensor_elems(shape->batch, shape->n_kv_heads, L_kv, shape->d_head, &n)) return FEDRAG_ERR_SHAPE;
+    const size_t bytes = (size_t)n * elem_size(shape->dtype);
+    if (!aligned16(K) || !aligned16(V) || !aligned16(phi_k) || !aligned16(phi_v) || !aligned16(K_out) ||
+        !aligned16(V_out) || (reinterpret_cast<uintptr_t>(perm_kv) & 3u))
+        return FEDRAG_ERR_ALIAS;
+    if (overlaps(K_out, bytes, K, bytes) || overlaps(K_out, bytes, V, bytes) || overlaps(V_out, bytes, K, bytes) ||
+        overlaps(V_out, bytes, V, bytes) || overlaps(K_out, bytes, V_out, bytes))
+        return FEDRAG_ERR_ALIAS;
+    RowsJob j{};
+    j.n_jobs = 2;
+    j.X[0] = K; j.Phi[0] = phi_k; j.Y[0] = K_out;
+    j.X[1] = V; j.Phi[1] = phi_v; j.Y[1] = V_out;
+    j.perm = perm_kv;
+    j.perm_batch_stride = (perm_kv && n_perm > 1) ? L_kv : 0;
+    j.BH = (int64_t)shape->batch * shape->n_kv_heads;
+    j.H = shape->n_kv_heads;
+    j.G = 1;
+    j.L = L_kv;
+    j.D = shape->d_head;
+    j.dtype = shape->dtype;
+    j.scatter = false;
+    return dev(launch_rows_transform(j, (hipStream_t)stream));
+}
+
+fedrag_status fedrag_scramble_q(const fedrag_shape* shape, int64_t L_q, const void* Q, const void* phi_q,
+                                const int32_t* perm_q, void* Q_out, void* stream) {
+    fedrag_status st = check_shape(shape, true);
+    if (st != FEDRAG_OK) return st;
+    if (L_q < 0 || L_q > INT32_MAX) return FEDRAG_ERR_SHAPE;
+    if (!Q || !phi_q || !Q_out) return FEDRAG_ERR_NULL;
+    int64_t n;
+    if (!tensor_elems(shape->batch, shape->n_q_heads, L_q, shape->d_head, &n)) return FEDRAG_ERR_SHAPE;
+    const size_t bytes = (size_t)n * elem_size(shape->dtype);
+    if (!aligned16(Q) || !aligned16(phi_q) || !aligned16(Q_out) || (reinterpret_cast<uintptr_t>(perm_q) & 3u))
+        return FEDRAG_ERR_ALIAS;
+    if (overlaps(Q_out, bytes, Q, bytes)) return FEDRAG_ERR_ALIAS;
+    RowsJob j{};
+    j.n_jobs = 1;
+    j.X[0] = Q; j.Phi[0] = phi_q; j.Y[0] = Q_out;
+    j.X[1] = Q; j.Phi[1] = phi_q; j.Y[1] = Q_out;
+    j.perm = perm_q;
+    j.perm_batch_stride = 0;
+    j.BH = (int64_t)shape->batch * shape->n_q_heads;
+    j.H = shape->n_q_heads;
+    j.G = shape->n_q_heads / shape->n_kv_heads;
+    j.L = L_q;
+    j.D = shape->d_head;
+    j.dtype = shape->dtype;
+    j.scatter = false;
+    return dev(launch_rows_transform(j, (hipStream_t)stream));
+}
+
+size_t fedrag_partial_attn_workspace_bytes(const fedrag_shape* shape, int64_t L_q, int64_t L_kv) {
+    if (check_shape(shape, true) != FEDRAG_OK || L_q < 0 || L_kv < 0) return 0;
+    return attn_workspace_bytes(shape->batch, shape->n_q_heads, shape->n_kv_heads, shape->d_head, shape->dtype, L_q,
+                                L_kv);
+}
+
+fedrag_status fedrag_partial_attn(const fedrag_shape* shape, int64_t L_q, int64_t L_kv, const void* Qs,
+                                  const void* Ks, const void* Vs, float softmax_scale, float* O_part, float* lse,
+                                  void* workspace, size_t workspace_bytes, void* stream) {
+    fedrag_status st = check_shape(shape, true);
+    if (st != FEDRAG_OK) return st;
+    if (L_q < 0 || L_kv < 0) return FEDRAG_ERR_SHAPE;
+    if (!Qs || !O_part || !lse) return FEDRAG_ERR_NULL;
+    if (L_kv > 0 && (!Ks || !Vs)) return FEDRAG_ERR_NULL;
+    int64_t nq, nk;
+    if (!tensor_elems(shape->batch, shape->n_q_heads, L_q, shape->d_head, &nq) ||
+        !tensor_elems(shape->batch, shape->n_kv_heads, L_kv, shape->d_head, &nk))
+        return FEDRAG_ERR_SHAPE;
+    if (!(softmax_scale == softmax_scale) || softmax_scale - softmax_scale != 0.0f) return FEDRAG_ERR_SHAPE;
+    if (!aligned16(Qs) || !aligned16(Ks) || !aligned16(Vs) || !aligned16(O_part) ||
+        (reinterpret_cast<uintptr_t>(lse) & 3u) || !aligned16(workspace))
+        return FEDRAG_ERR_ALIAS;
+    const size_t need = attn_workspace_bytes(shape->batch, shape->n_q_heads, shape->n_kv_heads, shape->d_head,
+                                             shape->dtype, L_q, L_kv);
+    if (need > 0 && (!workspace || workspace_bytes < need)) return FEDRAG_ERR_WORKSPACE;
+    AttnProblem p{};
+    p.B = shape->batch; p.Hq = shape->n_q_heads; p.Hkv = shape->n_kv_heads; p.D = shape->d_head;
+    p.dtype = shape->dtype;
+    p.Lq = L_q; p.Lkv = L_kv;
+    p.Q = Qs; p.K = Ks; p.V = Vs;
+    p.scale = softmax_scale;
+    p.O = O_part; p.lse = lse;
+    p.workspace = workspace; p.workspace_bytes = workspace_bytes;
+    return dev(launch_partial_attn(p, (hipStream_t)stream));
+}
+
+fedrag_status fedrag_lse_merge(const fedrag_shape* shape, int64_t L_q, int32_t n_shards, const float* O_parts,
+                               const float* lses, float* O_out, float* lse_out, void* stream) {
+    fedrag_status st = check_shape(shape, false);
+    if (st != FEDRAG_OK) return st;
+    if (L_q < 0 || n_shards < 1) return FEDRAG_ERR_SHAPE;
+    if (!O_parts || !lses || !O_out || !lse_out) return FEDRAG_ERR_NULL;
+    int64_t n;
+    if (!tensor_elems(shape->batch, shape->n_q_heads, L_q, shape->d_head, &n)) return FEDRAG_ERR_SHAPE;
+    if (n > INT64_MAX / 8 / n_shards) return FEDRAG_ERR_SHAPE;
+    const int64_t rows = n / shape->d_head;
+    if (!aligned16(O_parts) || !aligned16(O_out) || (reinterpret_cast<uintptr_t>(lses) & 3u) ||
+        (reinterpret_cast<uintptr_t>(lse_out) & 3u))
+        return FEDRAG_ERR_ALIAS;
+    if (overlaps(O_out, (size_t)n * 4, O_parts, (size_t)n * 4 * n_shards) ||
+        overlaps(lse_out, (size_t)rows * 4, lses, (size_t)rows * 4 * n_shards))
+        return FEDRAG_ERR_ALIAS;
+    return dev(launch_lse_merge(O_parts, lses, n_shards, rows, shape->d_head, O_out, lse_out, (hipStream_t)stream));
+}
+
+fedrag_status fedrag_unscramble(const fedrag_shape* shape, int64_t L_q, const float* O_scr, const float* phi_v_inv,
+                                const int32_t* perm_q, float* O_out, void* stream) {
+    fedrag_status st = check_shape(shape, false);
+    if (st != FEDRAG_OK) return st;
+    if (L_q < 0 || L_q > INT32_MAX) return FEDRAG_ERR_SHAPE;
+    if (!O_scr || !phi_v_inv || !O_out) return FEDRAG_ERR_NULL;
+    int64_t n;
+    if (!tensor_elems(shape->batch, shape->n_q_heads, L_q, shape->d_head, &n)) return FEDRAG_ERR_SHAPE;
+    if (!aligned16(O_scr) || !aligned16(phi_v_inv) || !aligned16(O_out) || (reinterpret_cast<uintptr_t>(perm_q) & 3u))
+        return FEDRAG_ERR_ALIAS;
+    if (overlaps(O_out, (size_t)n * 4, O_scr, (size_t)n * 4)) return FEDRAG_ERR_ALIAS;
+    RowsJob j{};
+    j.n_jobs = 1;
+    j.X[0] = O_scr; j.Phi[0] = phi_v_inv; j.Y[0] = O_out;
+    j.X[1] = O_scr; j.Phi[1] = phi_v_inv; j.Y[1] = O_out;
+    j.perm = perm_q;
+    j.perm_batch_stride = 0;
+    j.BH = (int64_t)shape->batch * shape->n_q_heads;
+    j.H = shape->n_q_heads;
+    j.G = shape->n_q_heads / shape->n_kv_heads;
+    j.L = L_q;
+    j.D = shape->d_head;
+    j.dtype = FEDRAG_F32;
+    j.scatter = true;
+    return dev(launch_rows_transform(j, (hipStream_t)stream));
+}
+
+fedrag_status fedrag_invert_perm(const int32_t* perm, int64_t L, int32_t* inv_out, void* stream) {
+    if (L < 0 || L > INT32_MAX) return FEDRAG_ERR_SHAPE;
+    if (!perm || !inv_out) return FEDRAG_ERR_NULL;
+    if ((reinterpret_cast<uintptr_t>(perm) & 3u) || (reinterpret_cast<uintptr_t>(inv_out) & 3u)) return FEDRAG_ERR_ALIAS;
+    if (overlaps(perm, (size_t)L * 4, inv_out, (size_t)L * 4)) return FEDRAG_ERR_ALIAS;
+    return dev(launch_invert_perm(perm, L, inv_out, (hipStream_t)stream));
+}
+
+const char* fedrag_status_string(fedrag_status status) {
+    switch (status) {
+        case FEDRAG_OK: return "ok";
+        case FEDRAG_ERR_NULL: return "a required pointer is NULL";
+        case FEDRAG_ERR_SHAPE: return "invalid shape or size argument";
+        case FEDRAG_ERR_UNSUPPORTED: return "unsupported d_head or dtype";
+        case FEDRAG_ERR_WORKSPACE: return "workspace missing or too small";
+        case FEDRAG_ERR_ALIAS: return "output overlaps an input, or a pointer is misaligned";
+        case FEDRAG_ERR_DEVICE: return "HIP launch failed";
+    }
+    return "unknown status";
+}
+
+int fedrag_version(void) { return 100; }
+
+}  // extern "C"

@@ -1,0 +1,52 @@
+// Host-side internal interface between the C-ABI entry points (fedrag_api.hip) and the kernel launchers.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/fedrag.h"
+
+namespace fedrag {
+
+// Rows-times-matrix job: up to two tensors (K and V) transformed in one launch.
+struct RowsJob {
+    int n_jobs;               // 1 or 2
+    const void* X[2];
+    const void* Phi[2];       // [Hkv, D, D]
+    void* Y[2];
+    const int32_t* perm;      // NULL = identity
+    int64_t perm_batch_stride;  // 0 (one permutation for all sequences) or L
+    int64_t BH;               // batch * heads
+    int H;                    // heads per sequence
+    int G;                    // heads per scrambling matrix
+    int64_t L;                // rows per (batch, head)
+    int D;                    // 64 or 128
+    int dtype;                // fedrag_dtype of X / Phi / Y (ignored when scatter: fp32)
+    bool scatter;             // false: Y[j] = X[perm[j]].Phi ; true: Y[perm[i]] = X[i].Phi (fp32)
+};
+hipError_t launch_rows_transform(const RowsJob& job, hipStream_t stream);
+hipError_t launch_invert_perm(const int32_t* perm, int64_t L, int32_t* inv, hipStream_t stream);
+
+// Partial attention problem (one KV shard).
+struct AttnProblem {
+    int B, Hq, Hkv, D, dtype;
+    int64_t Lq, Lkv;
+    const void *Q, *K, *V;
+    float scale;
+    float* O;     // [B,Hq,Lq,D]
+    float* lse;   // [B,Hq,Lq]
+    void* workspace;
+    size_t workspace_bytes;
+};
+// How the launcher will split the shard's keys across workgroups (1 = no workspace needed).
+int attn_kv_splits(int B, int Hq, int Hkv, int D, int dtype, int64_t Lq, int64_t Lkv);
+size_t attn_workspace_bytes(int B, int Hq, int Hkv, int D, int dtype, int64_t Lq, int64_t Lkv);
+hipError_t launch_partial_attn(const AttnProblem& p, hipStream_t stream);
+
+// Aggregation of S partials: O_parts [S, rows, D], lses [S, rows] -> O [rows, D], lse [rows].
+hipError_t launch_lse_merge(const float* O_parts, const float* lses, int S, int64_t rows, int D, float* O, float* lse,
+                            hipStream_t stream);
+// O = 0, lse = -inf for `rows` rows (a shard with no keys).
+hipError_t launch_fill_empty(float* O, float* lse, int64_t rows, int D, hipStream_t stream);
+
+}  // namespace fedrag

@@ -1,0 +1,269 @@
+// Enc / Dec row transforms (Section 4.2, scrambled attention protocol, steps 1 and 3):
+//   gather form   Y[j,:]       = X[perm[j],:] . Phi      (feature scramble + token permutation)
+//   scatter form  Y[perm[i],:] = X[i,:] . Phi            (descramble + inverse permutation)
+// One d x d matrix per KV head, shared by the G query heads of its group.
+//
+// 16-bit storage path: HBM-bound (each row is read once and written once, 2*d^2 flop per 4*d bytes), so the
+// d x d product runs on MFMA only to stay far below the memory time.  A wave owns 16 rows at a time:
+// rows are fetched with full-row coalesced 16-byte loads, staged through a wave-private LDS tile into the
+// MFMA operand layout, multiplied against Phi^T held in registers for the whole kernel, and the fp32
+// results are narrowed once (RNE), transposed back through the same LDS tile and stored as full rows.
+#include "fedrag_device.h"
+#include "fedrag_host.h"
+
+namespace fedrag {
+
+constexpr int kScrWaves = 4;
+constexpr int kScrThreads = kScrWaves * kWave;
+constexpr int kScrPad = 8;  // elements of row padding in LDS (16 bytes: keeps 16-byte alignment, breaks bank stride)
+
+struct ScrambleJob {
+    const void* X;
+    const void* Phi;
+    void* Y;
+};
+
+// blockIdx.x = (bh * chunks + chunk); blockIdx.y selects the job (K or V).
+template <class T, int D>
+__global__ __launch_bounds__(kScrThreads) void scramble_rows_kernel(ScrambleJob job0, ScrambleJob job1,
+                                                                    const int32_t* __restrict__ perm,
+                                                                    int64_t perm_batch_stride,  // 0 or L
+                                                                    int H, int G, int64_t L, int chunks,
+                                                                    int tiles_per_wave) {
+    typedef typename T::elem elem;
+    typedef typename T::vec8 vec8;
+    typedef typename T::vec4 vec4;
+    constexpr int LDP = D + kScrPad;
+    constexpr int CH = D / 8;          // 16-byte chunks per row
+    constexpr int RPI = kWave / CH;    // rows covered by one wave-wide 16-byte load
+    constexpr int NI = 16 / RPI;       // wave-wide loads per 16-row tile
+    constexpr int KS = D / 32;         // contraction steps
+    constexpr int MT = D / 16;         // output-column tiles
+
+    __shared__ __attribute__((aligned(16))) elem phiT[D * LDP];             // Phi^T: [n][k]
+    __shared__ __attribute__((aligned(16))) elem tile[kScrWaves][16 * LDP];  // per-wave row tile
+
+    const ScrambleJob job = blockIdx.y == 0 ? job0 : job1;
+    const int tid = threadIdx.x;
+    const int wave = tid / kWave;
+    const int lane = tid % kWave;
+    const int bh = blockIdx.x / chunks;
+    const int chunk = blockIdx.x % chunks;
+    const int b = bh / H;
+    const int h = bh % H;
+
+    // ---- stage Phi^T[n][k] = Phi[k][n] in LDS (once per workgroup) ----
+    {
+        const elem* P = (const elem*)job.Phi + (int64_t)(h / G) * D * D;
+        for (int c = tid; c < D * CH; c += kScrThreads) {
+            const int k = c / CH;
+            const int n0 = (c % CH) * 8;
+            const vec8 v = *(const vec8*)(P + k * D + n0);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) phiT[(n0 + e) * LDP + k] = v[e];
+        }
+    }
+    __syncthreads();
+
+    // Phi^T operands for the whole kernel: phi[mt][ks] = Phi^T[16 mt + lane%16][32 ks + 8 (lane/16) .. +8]
+    const int lr = lane % 16;
+    const int lq = lane / 16;
+    vec8 phi[MT][KS];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+            phi[mt][ks] = *(const vec8*)(&phiT[(mt * 16 + lr) * LDP + ks * 32 + lq * 8]);
+
+    const elem* X = (const elem*)job.X + (int64_t)bh * L * D;
+    elem* Y = (elem*)job.Y + (int64_t)bh * L * D;
+    const int32_t* pm = perm ? perm + (int64_t)b * perm_batch_stride : nullptr;
+    elem* my = tile[wave];
+
+    const int ld_row = lane / CH;        // row within one wave-wide load
+    const int ld_col = (lane % CH) * 8;  // element offset of this lane's 16 bytes
+
+    const int64_t chunk_row0 = (int64_t)chunk * tiles_per_wave * kScrWaves * 16;
+
+    auto load_tile = [&](int64_t row0, vec8 (&buf)[NI]) {
+#pragma unroll
+        for (int i = 0; i < NI; ++i) {
+            int64_t j = row0 + i * RPI + ld_row;
+            if (j >= L) j = L - 1;  // clamp: rows past the end are computed but never stored
+            const int64_t src = pm ? (int64_t)pm[j] : j;
+            buf[i] = *(const vec8*)(X + src * D + ld_col);
+        }
+    };
+
+    vec8 cur[NI];
+    int64_t row0 = chunk_row0 + (int64_t)wave * 16;
+    if (row0 < L) load_tile(row0, cur);
+
+    for (int t = 0; t < tiles_per_wave; ++t, row0 += kScrWaves * 16) {
+        if (row0 >= L) break;  // wave-uniform
+        // rows -> LDS tile
+#pragma unroll
+        for (int i = 0; i < NI; ++i) *(vec8*)(&my[(i * RPI + ld_row) * LDP + ld_col]) = cur[i];
+        wave_lds_fence();
+        // prefetch the next tile of this wave while this one is multiplied
+        const int64_t next0 = row0 + kScrWaves * 16;
+        if (t + 1 < tiles_per_wave && next0 < L) load_tile(next0, cur);
+
+        // X^T operands: column = row lane%16 of the tile, contraction slice 32 ks + 8 (lane/16)
+        vec8 xop[KS];
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) xop[ks] = *(const vec8*)(&my[lr * LDP + ks * 32 + lq * 8]);
+
+        // Y^T tile (d x 16 rows) = Phi^T . X^T : lane holds row lane%16 of the tile, output columns 16 mt + 4 lq + r
+        f32x4_t acc[MT];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+            acc[mt] = zero_vec<f32x4_t>();
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) acc[mt] = T::mfma16(phi[mt][ks], xop[ks], acc[mt]);
+        }
+        wave_lds_fence();  // all operand reads done before the tile is overwritten
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+            vec4 o;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) o[r] = T::from_float(acc[mt][r]);
+            *(vec4*)(&my[lr * LDP + mt * 16 + lq * 4]) = o;
+        }
+        wave_lds_fence();
+        // full-row stores
+#pragma unroll
+        for (int i = 0; i < NI; ++i) {
+            const int64_t j = row0 + i * RPI + ld_row;
+            const vec8 v = *(const vec8*)(&my[(i * RPI + ld_row) * LDP + ld_col]);
+            if (j < L) *(vec8*)(Y + j * D + ld_col) = v;
+        }
+        wave_lds_fence();  // reads of the output tile done before the next tile's rows land
+    }
+}
+
+// fp32 rows times fp32 matrix with plain FMAs (fp32 storage path of Enc, and Dec for every storage type).
+// Thread (c, rg) owns output column c and holds column c of Phi in registers; rows are broadcast from LDS.
+//   SCATTER == false: Y[j]       = X[perm[j]] . Phi   (perm NULL = identity)
+//   SCATTER == true : Y[perm[i]] = X[i] . Phi
+constexpr int kF32Threads = 256;
+constexpr int kF32Rows = 32;
+
+template <int D, bool SCATTER>
+__global__ __launch_bounds__(kF32Threads) void rows_times_matrix_f32_kernel(ScrambleJob job0, ScrambleJob job1,
+                                                                            const int32_t* __restrict__ perm,
+                                                                            int64_t perm_batch_stride, int H, int G,
+                                                                            int64_t L, int chunks, int tiles_per_wg) {
+    constexpr int RG = kF32Threads / D;  // row groups
+    __shared__ __attribute__((aligned(16))) float xs[kF32Rows * D];
+    const ScrambleJob job = blockIdx.y == 0 ? job0 : job1;
+    const int tid = threadIdx.x;
+    const int c = tid % D;
+    const int rg = tid / D;
+    const int bh = blockIdx.x / chunks;
+    const int chunk = blockIdx.x % chunks;
+    const int b = bh / H;
+    const int h = bh % H;
+    const float* P = (const float*)job.Phi + (int64_t)(h / G) * D * D;
+    float phi[D];
+#pragma unroll
+    for (int k = 0; k < D; ++k) phi[k] = P[k * D + c];
+
+    const float* X = (const float*)job.X + (int64_t)bh * L * D;
+    float* Y = (float*)job.Y + (int64_t)bh * L * D;
+    const int32_t* pm = perm ? perm + (int64_t)b * perm_batch_stride : nullptr;
+
+    int64_t row0 = (int64_t)chunk * tiles_per_wg * kF32Rows;
+    for (int t = 0; t < tiles_per_wg && row0 < L; ++t, row0 += kF32Rows) {
+        __syncthreads();
+        for (int e = tid; e < kF32Rows * (D / 4); e += kF32Threads) {
+            const int r = e / (D / 4);
+            const int c4 = (e % (D / 4)) * 4;
+            int64_t j = row0 + r;
+            if (j >= L) j = L - 1;
+            const int64_t src = (!SCATTER && pm) ? (int64_t)pm[j] : j;
+            *(f32x4_t*)(&xs[r * D + c4]) = *(const f32x4_t*)(X + src * D + c4);
+        }
+        __syncthreads();
+        for (int r = rg; r < kF32Rows; r += RG) {
+            const int64_t j = row0 + r;
+            if (j >= L) break;
+            float acc = 0.f;
+#pragma unroll
+            for (int k4 = 0; k4 < D; k4 += 4) {
+                const f32x4_t x = *(const f32x4_t*)(&xs[r * D + k4]);
+                acc = __builtin_fmaf(x[0], phi[k4 + 0], acc);
+                acc = __builtin_fmaf(x[1], phi[k4 + 1], acc);
+                acc = __builtin_fmaf(x[2], phi[k4 + 2], acc);
+                acc = __builtin_fmaf(x[3], phi[k4 + 3], acc);
+            }
+            const int64_t dst = (SCATTER && pm) ? (int64_t)pm[j] : j;
+            Y[dst * D + c] = acc;
+        }
+    }
+}
+
+__global__ void invert_perm_kernel(const int32_t* __restrict__ perm, int64_t L, int32_t* __restrict__ inv) {
+    const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (j < L) inv[perm[j]] = (int32_t)j;
+}
+
+// ------------------------------------------------------------------------------------------------ launchers
+static int ceil_div_i64(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
+
+template <class T, int D>
+static hipError_t launch_scramble16(const RowsJob& j, hipStream_t stream) {
+    const int64_t tiles64 = (j.L + 63) / 64;  // 64 rows = one pass of the 4 waves
+    // aim at ~4 workgroups per CU over the whole launch so that Phi staging is amortised
+    const int64_t want_wgs = 1024;
+    const int64_t total = tiles64 * j.BH * j.n_jobs;
+    int tpw = (int)((total + want_wgs - 1) / want_wgs);
+    if (tpw < 1) tpw = 1;
+    if (tpw > 64) tpw = 64;
+    const int chunks = ceil_div_i64(tiles64, tpw);
+    dim3 grid((unsigned)(j.BH * chunks), (unsigned)j.n_jobs);
+    ScrambleJob a{j.X[0], j.Phi[0], j.Y[0]}, b{j.X[1], j.Phi[1], j.Y[1]};
+    hipLaunchKernelGGL((scramble_rows_kernel<T, D>), grid, dim3(kScrThreads), 0, stream, a, b, j.perm,
+                       j.perm_batch_stride, j.H, j.G, j.L, chunks, tpw);
+    return hipGetLastError();
+}
+
+template <int D, bool SCATTER>
+static hipError_t launch_rows_f32(const RowsJob& j, hipStream_t stream) {
+    const int64_t tiles = (j.L + kF32Rows - 1) / kF32Rows;
+    const int64_t want_wgs = 2048;
+    const int64_t total = tiles * j.BH * j.n_jobs;
+    int tpw = (int)((total + want_wgs - 1) / want_wgs);
+    if (tpw < 1) tpw = 1;
+    if (tpw > 64) tpw = 64;
+    const int chunks = ceil_div_i64(tiles, tpw);
+    dim3 grid((unsigned)(j.BH * chunks), (unsigned)j.n_jobs);
+    ScrambleJob a{j.X[0], j.Phi[0], j.Y[0]}, b{j.X[1], j.Phi[1], j.Y[1]};
+    hipLaunchKernelGGL((rows_times_matrix_f32_kernel<D, SCATTER>), grid, dim3(kF32Threads), 0, stream, a, b, j.perm,
+                       j.perm_batch_stride, j.H, j.G, j.L, chunks, tpw);
+    return hipGetLastError();
+}
+
+hipError_t launch_rows_transform(const RowsJob& j, hipStream_t stream) {
+    if (j.L == 0 || j.BH == 0) return hipSuccess;
+    if (j.scatter) {  // Dec: always fp32
+        return j.D == 128 ? launch_rows_f32<128, true>(j, stream) : launch_rows_f32<64, true>(j, stream);
+    }
+    switch (j.dtype) {
+        case FEDRAG_F32:
+            return j.D == 128 ? launch_rows_f32<128, false>(j, stream) : launch_rows_f32<64, false>(j, stream);
+        case FEDRAG_BF16:
+            return j.D == 128 ? launch_scramble16<BF16, 128>(j, stream) : launch_scramble16<BF16, 64>(j, stream);
+        case FEDRAG_F16:
+            return j.D == 128 ? launch_scramble16<F16, 128>(j, stream) : launch_scramble16<F16, 64>(j, stream);
+    }
+    return hipErrorInvalidValue;
+}
+
+hipError_t launch_invert_perm(const int32_t* perm, int64_t L, int32_t* inv, hipStream_t stream) {
+    if (L == 0) return hipSuccess;
+    hipLaunchKernelGGL(invert_perm_kernel, dim3((unsigned)((L + 255) / 256)), dim3(256), 0, stream, perm, L, inv);
+    return hipGetLastError();
+}
+
+}  // namespace fedrag

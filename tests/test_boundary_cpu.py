@@ -1,0 +1,141 @@
+"""Host-side logic of the C-ABI library, runnable without a GPU: the library loads, exports every symbol the
+header declares, and every argument error is reported before any HIP call is made (so fake, never
+dereferenced pointers are safe here: each call below must fail validation)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2605_25716_amd import binding as fb
+from paper_2605_25716_amd import build as fbuild
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+A = 0x10000  # fake 16-byte aligned "device pointers"; validation never dereferences them
+
+
+@pytest.fixture(scope="module")
+def lib():
+    fbuild.build_library(force=False)
+    return fb.load()
+
+
+def shape(B=2, Hq=8, Hkv=2, d=128, dt=fb.BF16):
+    return fb.Shape(B, Hq, Hkv, d, dt)
+
+
+def P(x):
+    return ctypes.c_void_p(x)
+
+
+def test_library_exports_every_declared_symbol(lib):
+    header = open(os.path.join(ROOT, "include", "fedrag.h")).read()
+    declared = set(re.findall(r"\b(fedrag_[a-z_0-9]+)\s*\(", header))
+    assert declared == set(fb.EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert fb.version() >= 100
+    for code in range(7):
+        assert fb.status_string(code) and fb.status_string(code) != "unknown status"
+    assert fb.status_string(99) == "unknown status"
+
+
+def test_scramble_kv_validation(lib):
+    s = shape()
+    f = lib.fedrag_scramble_kv
+    ok_args = lambda: [ctypes.byref(s), 64, P(A), P(2 * A), P(3 * A), P(4 * A), P(5 * A), 1, P(6 * A), P(7 * A), None]
+    a = ok_args(); a[0] = None
+    assert f(*a) == fb.ERR_NULL
+    for i in (2, 3, 4, 5, 8, 9):
+        a = ok_args(); a[i] = None
+        assert f(*a) == fb.ERR_NULL
+    a = ok_args(); a[1] = -1
+    assert f(*a) == fb.ERR_SHAPE
+    a = ok_args(); a[7] = 3          # n_perm neither 1 nor B
+    assert f(*a) == fb.ERR_SHAPE
+    a = ok_args(); a[8] = P(A)       # K_out aliases K
+    assert f(*a) == fb.ERR_ALIAS
+    a = ok_args(); a[9] = P(A + 256)  # V_out overlaps K
+    assert f(*a) == fb.ERR_ALIAS
+    a = ok_args(); a[2] = P(A + 4)   # misaligned
+    assert f(*a) == fb.ERR_ALIAS
+    bad = shape(Hq=6, Hkv=4); a = ok_args(); a[0] = ctypes.byref(bad)
+    assert f(*a) == fb.ERR_SHAPE
+    bad = shape(d=96); a = ok_args(); a[0] = ctypes.byref(bad)
+    assert f(*a) == fb.ERR_UNSUPPORTED
+    bad = shape(dt=7); a = ok_args(); a[0] = ctypes.byref(bad)
+    assert f(*a) == fb.ERR_UNSUPPORTED
+
+
+def test_scramble_q_and_unscramble_validation(lib):
+    s = shape()
+    assert lib.fedrag_scramble_q(ctypes.byref(s), 4, None, P(A), None, P(2 * A), None) == fb.ERR_NULL
+    assert lib.fedrag_scramble_q(ctypes.byref(s), -4, P(A), P(2 * A), None, P(3 * A), None) == fb.ERR_SHAPE
+    assert lib.fedrag_scramble_q(ctypes.byref(s), 4, P(A), P(2 * A), None, P(A), None) == fb.ERR_ALIAS
+    assert lib.fedrag_scramble_q(ctypes.byref(s), 4, P(A), P(2 * A), P(3 * A + 2), P(4 * A), None) == fb.ERR_ALIAS
+    assert lib.fedrag_unscramble(ctypes.byref(s), 4, P(A), None, None, P(2 * A), None) == fb.ERR_NULL
+    assert lib.fedrag_unscramble(ctypes.byref(s), 4, P(A), P(3 * A), None, P(A + 16), None) == fb.ERR_ALIAS
+    bad = shape(d=32)
+    assert lib.fedrag_unscramble(ctypes.byref(bad), 4, P(A), P(3 * A), None, P(2 * A), None) == fb.ERR_UNSUPPORTED
+
+
+def test_partial_attn_validation_and_workspace(lib):
+    s = shape(B=16, Hq=32, Hkv=8)
+    need = lib.fedrag_partial_attn_workspace_bytes(ctypes.byref(s), 1, 8192)
+    assert need > 0 and need % 4 == 0
+    f = lib.fedrag_partial_attn
+    base = lambda: [ctypes.byref(s), 1, 8192, P(A), P(2 * A), P(3 * A), ctypes.c_float(0.088), P(4 * A), P(5 * A),
+                    P(6 * A), need, None]
+    a = base(); a[10] = need - 1
+    assert f(*a) == fb.ERR_WORKSPACE
+    a = base(); a[9] = None
+    assert f(*a) == fb.ERR_WORKSPACE
+    a = base(); a[3] = None
+    assert f(*a) == fb.ERR_NULL
+    a = base(); a[4] = None
+    assert f(*a) == fb.ERR_NULL
+    a = base(); a[7] = None
+    assert f(*a) == fb.ERR_NULL
+    a = base(); a[2] = -5
+    assert f(*a) == fb.ERR_SHAPE
+    a = base(); a[6] = ctypes.c_float(float("nan"))
+    assert f(*a) == fb.ERR_SHAPE
+    a = base(); a[3] = P(A + 8)
+    assert f(*a) == fb.ERR_ALIAS
+    # workspace query: prefill-shaped and fp32 problems need none; bad shapes report 0
+    assert lib.fedrag_partial_attn_workspace_bytes(ctypes.byref(s), 2048, 16384) == 0
+    s32 = shape(dt=fb.F32)
+    assert lib.fedrag_partial_attn_workspace_bytes(ctypes.byref(s32), 1, 8192) == 0
+    assert lib.fedrag_partial_attn_workspace_bytes(ctypes.byref(shape(d=100)), 1, 8192) == 0
+    # splits x rows x (d + 1) floats
+    rows = 16 * 32
+    assert need % (rows * 129 * 4) == 0 and 2 <= need // (rows * 129 * 4) <= 64
+
+
+def test_merge_and_invert_perm_validation(lib):
+    s = shape()
+    f = lib.fedrag_lse_merge
+    assert f(ctypes.byref(s), 1, 0, P(A), P(2 * A), P(3 * A), P(4 * A), None) == fb.ERR_SHAPE
+    assert f(ctypes.byref(s), 1, 2, None, P(2 * A), P(3 * A), P(4 * A), None) == fb.ERR_NULL
+    assert f(ctypes.byref(s), 1, 2, P(A), P(2 * A), P(A), P(4 * A), None) == fb.ERR_ALIAS
+    assert f(ctypes.byref(s), 1, 2, P(A), P(2 * A), P(3 * A), P(2 * A), None) == fb.ERR_ALIAS
+    g = lib.fedrag_invert_perm
+    assert g(None, 4, P(A), None) == fb.ERR_NULL
+    assert g(P(A), -1, P(2 * A), None) == fb.ERR_SHAPE
+    assert g(P(A), 8, P(A + 16), None) == fb.ERR_ALIAS
+
+
+def test_zero_sized_problems_are_ok_without_a_device(lib):
+    # nothing to do: returns OK before any launch
+    s = shape(B=0)
+    assert lib.fedrag_scramble_q(ctypes.byref(s), 4, P(A), P(2 * A), None, P(3 * A), None) == fb.OK
+    s = shape()
+    assert lib.fedrag_scramble_q(ctypes.byref(s), 0, P(A), P(2 * A), None, P(3 * A), None) == fb.OK
+    assert lib.fedrag_invert_perm(P(A), 0, P(2 * A), None) == fb.OK
+
+
+def test_binding_refuses_cpu_tensors(lib):
+    import torch
+    q = torch.zeros(1, 2, 1, 64)
+    with pytest.raises(ValueError):
+        fb.fedrag_scramble_q(q, torch.zeros(2, 64, 64))
