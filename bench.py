@@ -1,0 +1,241 @@
+#!/usr/bin/env python3
+"""Benchmark of the hot path on one MI355X.
+
+A step is one pass of all five calls over the Llama-3-8B-shaped decode workload (batch 16, 32 query / 8 KV
+heads, d 128, 4 shards of 8192 tokens, bf16): scramble_q, then per shard scramble_kv and partial_attn, then
+lse_merge and unscramble.  `value` is the step's algorithmic HBM bytes divided by the step time.  The same
+JSON line carries the roofline of the kernel that dominates the step, per-call figures, the RAG-prefill
+TFLOP/s (2048 queries x 16384 keys) and the CPU oracle timed on a bounded sample of the same workload.
+
+    python bench.py --gpus 1 --steps 20 --warmup 3
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16 MFMA
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--no-prefill", action="store_true", help="skip the RAG-prefill leg")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
+    ap.add_argument("--cpu-seqs", type=int, default=4, help="sequences of shard 0 the oracle is timed on")
+    return ap.parse_args()
+
+
+class CallTimer:
+    """HIP events on the stream the kernels are launched on (torch's current stream)."""
+
+    def __init__(self, torch):
+        self.torch = torch
+        self.pairs = {}
+
+    def run(self, name, fn):
+        a = self.torch.cuda.Event(enable_timing=True)
+        b = self.torch.cuda.Event(enable_timing=True)
+        a.record()
+        out = fn()
+        b.record()
+        self.pairs.setdefault(name, []).append((a, b))
+        return out
+
+    def summary(self):
+        out = {}
+        for name, pairs in self.pairs.items():
+            ms = [a.elapsed_time(b) for a, b in pairs]
+            out[name] = {"calls": len(ms), "avg_us": 1e3 * sum(ms) / len(ms), "total_ms": sum(ms)}
+        return out
+
+
+def decode_workload(torch, W, fb, dev):
+    cfg = W.CONFIGS["llama8b_decode"]
+    dt = W.torch_dtype(cfg.dtype)
+    keys = W.make_keys(cfg.n_kv_heads, cfg.d_head, cfg.L_q, cfg.L_kv, cfg.n_shards, seed=cfg.seed, dtype=dt)
+    g = {
+        "cfg": cfg,
+        "Q": W.activations(cfg.batch, cfg.n_q_heads, cfg.L_q, cfg.d_head, seed=cfg.seed, tensor_id=W.TID_Q,
+                           outliers=True, dtype=dt, device=dev),
+        "K": [W.activations(cfg.batch, cfg.n_kv_heads, cfg.L_kv, cfg.d_head, seed=cfg.seed, tensor_id=W.TID_K + s,
+                            outliers=True, outlier_id=W.TID_K, dtype=dt, device=dev) for s in range(cfg.n_shards)],
+        "V": [W.activations(cfg.batch, cfg.n_kv_heads, cfg.L_kv, cfg.d_head, seed=cfg.seed, tensor_id=W.TID_V + s,
+                            outliers=True, outlier_id=W.TID_V, dtype=dt, device=dev) for s in range(cfg.n_shards)],
+        "keys": keys,
+    }
+    k = keys
+    g["phi_q"], g["phi_k"], g["phi_v"], g["phi_v_inv"] = (t.to(dev) for t in (k.phi_q, k.phi_k, k.phi_v, k.phi_v_inv))
+    g["perm_kv"] = [p.to(dev) for p in k.perm_kv]
+    B, Hq, Hkv, d, Lq, L, S = cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.d_head, cfg.L_q, cfg.L_kv, cfg.n_shards
+    g["Qs"] = torch.empty_like(g["Q"])
+    g["Ks"] = [torch.empty_like(x) for x in g["K"]]
+    g["Vs"] = [torch.empty_like(x) for x in g["V"]]
+    g["O_parts"] = torch.empty((S, B, Hq, Lq, d), dtype=torch.float32, device=dev)
+    g["lses"] = torch.empty((S, B, Hq, Lq), dtype=torch.float32, device=dev)
+    g["O"] = torch.empty((B, Hq, Lq, d), dtype=torch.float32, device=dev)
+    g["lse"] = torch.empty((B, Hq, Lq), dtype=torch.float32, device=dev)
+    g["out"] = torch.empty((B, Hq, Lq, d), dtype=torch.float32, device=dev)
+    ws = fb.fedrag_partial_attn_workspace_bytes(B, Hq, Hkv, d, dt, Lq, L)
+    g["ws"] = torch.empty(max(ws, 16), dtype=torch.uint8, device=dev)
+    es = 2
+    kv_bytes = B * Hkv * L * d * es * 2          # K' + V' of one shard
+    g["bytes"] = {
+        "scramble_q": 2 * B * Hq * Lq * d * es,
+        "scramble_kv": 2 * kv_bytes + 4 * L,     # read K,V + write K',V' + the permutation
+        "partial_attn": kv_bytes + B * Hq * Lq * (d * es + d * 4 + 4),
+        "lse_merge": (S + 1) * B * Hq * Lq * (d + 1) * 4,
+        "unscramble": 2 * B * Hq * Lq * d * 4,
+    }
+    g["step_bytes"] = (g["bytes"]["scramble_q"] + S * (g["bytes"]["scramble_kv"] + g["bytes"]["partial_attn"]) +
+                       g["bytes"]["lse_merge"] + g["bytes"]["unscramble"])
+    return g
+
+
+def decode_step(fb, g, timer=None):
+    run = (lambda n, f: timer.run(n, f)) if timer else (lambda n, f: f())
+    cfg = g["cfg"]
+    run("scramble_q", lambda: fb.fedrag_scramble_q(g["Q"], g["phi_q"], None, Q_out=g["Qs"]))
+    for s in range(cfg.n_shards):
+        run("scramble_kv", lambda: fb.fedrag_scramble_kv(g["K"][s], g["V"][s], g["phi_k"], g["phi_v"], g["perm_kv"][s],
+                                                         n_q_heads=cfg.n_q_heads, K_out=g["Ks"][s], V_out=g["Vs"][s]))
+        run("partial_attn", lambda: fb.fedrag_partial_attn(g["Qs"], g["Ks"][s], g["Vs"][s], None,
+                                                           O_part=g["O_parts"][s], lse=g["lses"][s], workspace=g["ws"]))
+    run("lse_merge", lambda: fb.fedrag_lse_merge(g["O_parts"], g["lses"], n_kv_heads=cfg.n_kv_heads,
+                                                 O_out=g["O"], lse_out=g["lse"]))
+    run("unscramble", lambda: fb.fedrag_unscramble(g["O"], g["phi_v_inv"], None, O_out=g["out"]))
+
+
+def prefill_leg(torch, W, fb, dev, steps, warmup):
+    """RAG prefill: partial_attn alone, 2048 queries x 16384 keys, 32/8 heads, d 128, bf16."""
+    cfg = W.CONFIGS["rag_prefill"]
+    dt = W.torch_dtype(cfg.dtype)
+    mk = lambda H, L, tid, oid: W.activations(cfg.batch, H, L, cfg.d_head, seed=cfg.seed, tensor_id=tid, outliers=True,
+                                              outlier_id=oid, dtype=dt, device=dev)
+    Q, K, V = mk(cfg.n_q_heads, cfg.L_q, W.TID_Q, W.TID_Q), mk(cfg.n_kv_heads, cfg.L_kv, W.TID_K, W.TID_K), \
+        mk(cfg.n_kv_heads, cfg.L_kv, W.TID_V, W.TID_V)
+    keys = W.make_keys(cfg.n_kv_heads, cfg.d_head, cfg.L_q, cfg.L_kv, 1, seed=cfg.seed, dtype=dt)
+    Qs = fb.fedrag_scramble_q(Q, keys.phi_q.to(dev), keys.perm_q.to(dev))
+    Ks, Vs = fb.fedrag_scramble_kv(K, V, keys.phi_k.to(dev), keys.phi_v.to(dev), keys.perm_kv[0].to(dev))
+    O = torch.empty((cfg.batch, cfg.n_q_heads, cfg.L_q, cfg.d_head), dtype=torch.float32, device=dev)
+    lse = torch.empty((cfg.batch, cfg.n_q_heads, cfg.L_q), dtype=torch.float32, device=dev)
+    for _ in range(warmup):
+        fb.fedrag_partial_attn(Qs, Ks, Vs, None, O_part=O, lse=lse)
+    torch.cuda.synchronize()
+    timer = CallTimer(torch)
+    for _ in range(steps):
+        timer.run("partial_attn", lambda: fb.fedrag_partial_attn(Qs, Ks, Vs, None, O_part=O, lse=lse))
+    torch.cuda.synchronize()
+    t = timer.summary()["partial_attn"]
+    flop = 4.0 * cfg.L_q * cfg.L_kv * cfg.d_head * cfg.n_q_heads * cfg.batch
+    tflops = flop / (t["avg_us"] * 1e-6) / 1e12
+    return {"workload": "rag_prefill: B1 Hq32 Hkv8 d128 Lq2048 Lkv16384 bf16, non-causal", "flop": flop,
+            "avg_us": t["avg_us"], "value": tflops, "unit": "TFLOP/s",
+            "roofline": {"bound": "mfma", "achieved": tflops, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                         "frac": tflops / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
+                         "kernel": "prefill_attn_kernel<BF16,128>"}}
+
+
+def cpu_leg(torch, W, g, n_seqs):
+    """The oracle, as it stands, on shard 0 of the first n_seqs sequences: scramble_q, scramble K and V,
+    partial attention, merge (one shard), unscramble.  Bytes are the same algorithmic bytes, scaled."""
+    import oracle
+    cfg = g["cfg"]
+    n_seqs = min(n_seqs, cfg.batch)
+    Q = g["Q"][:n_seqs].cpu()
+    K = g["K"][0][:n_seqs].cpu()
+    V = g["V"][0][:n_seqs].cpu()
+    k = g["keys"]
+    perm = k.perm_kv[0]
+    t0 = time.perf_counter()
+    Qs = oracle.scramble(Q, k.phi_q, None)
+    Ks = oracle.scramble(K, k.phi_k, perm)
+    Vs = oracle.scramble(V, k.phi_v, perm)
+    o, l = oracle.partial_attn(Qs, Ks, Vs)
+    O, lse = oracle.lse_merge(o[None], l[None])
+    out = oracle.unscramble(O, k.phi_v_inv, None)
+    dt = time.perf_counter() - t0
+    frac = n_seqs / cfg.batch
+    b = g["bytes"]
+    nbytes = frac * (b["scramble_q"] + b["scramble_kv"] + b["partial_attn"] + b["unscramble"]) + \
+        2 * frac * b["lse_merge"] / (cfg.n_shards + 1)
+    return {"value": nbytes / dt / 1e9, "unit": "GB/s", "cores": oracle.get_threads(), "kind": "oracle",
+            "seconds": dt,
+            "sample": f"shard 0 of {cfg.n_shards}, sequences 0..{n_seqs - 1} of {cfg.batch}: all five calls in fp64 "
+                      f"({nbytes / 2**20:.0f} MiB of the step's algorithmic bytes)"}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (federation nodes are simulated as sequential KV shards "
+              "on that GPU); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2605_25716_amd import binding as fb
+    from paper_2605_25716_amd import build as fbuild
+    from paper_2605_25716_amd import workloads as W
+    if not os.path.exists(fbuild.LIB_PATH):
+        fbuild.build_library(force=True)
+    fb.load()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+
+    g = decode_workload(torch, W, fb, dev)
+    for _ in range(args.warmup):
+        decode_step(fb, g)
+    torch.cuda.synchronize()
+    timer = CallTimer(torch)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        decode_step(fb, g, timer)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = 1e3 * wall / args.steps
+    value = g["step_bytes"] / (ms_per_step * 1e-3) / 1e9
+
+    calls = timer.summary()
+    per_call = {}
+    for name, t in calls.items():
+        gbs = g["bytes"][name] / (t["avg_us"] * 1e-6) / 1e9
+        per_call[name] = {"avg_us": round(t["avg_us"], 2), "calls_per_step": t["calls"] // args.steps,
+                          "bytes": g["bytes"][name], "GB/s": round(gbs, 1), "frac_hbm": round(gbs / HBM_PEAK_GBS, 4)}
+    kernel_of = {"scramble_kv": "scramble_rows_kernel<BF16,128>", "partial_attn": "decode_attn_kernel<BF16,128>"}
+    dom = max(kernel_of, key=lambda n: calls[n]["total_ms"])
+    roofline = {"bound": "hbm", "achieved": per_call[dom]["GB/s"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(per_call[dom]["GB/s"] / HBM_PEAK_GBS, 4), "traffic": None,
+                "kernel": kernel_of[dom], "call": dom, "avg_us": per_call[dom]["avg_us"],
+                "bytes_per_launch": g["bytes"][dom]}
+    # the spec kernel on its own: K'/V' streaming of partial_attn (+ split merge) over the 4 shards
+    attn = per_call["partial_attn"]
+
+    line = {
+        "metric": "scrambled partial-attn: decode HBM GB/s + prefill TFLOP/s (% of peak)",
+        "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "llama8b_decode: B16 Hq32 Hkv8 d128 Lq1, 4 shards x 8192 tokens, bf16; "
+                               "step = scramble_q + 4x(scramble_kv + partial_attn) + lse_merge + unscramble",
+                   "step_bytes": g["step_bytes"]},
+        "roofline": roofline,
+        "decode_partial_attn": {"GB/s": attn["GB/s"], "frac_hbm": attn["frac_hbm"], "avg_us": attn["avg_us"]},
+        "calls": per_call,
+    }
+    if not args.no_prefill:
+        line["prefill"] = prefill_leg(torch, W, fb, dev, max(5, args.steps // 2), args.warmup)
+    if not args.no_cpu:
+        line["cpu_baseline"] = cpu_leg(torch, W, g, args.cpu_seqs)
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

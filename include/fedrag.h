@@ -16,7 +16,7 @@
  *   bijection on [0, L) is the caller's responsibility and is not checked on the hot path.
  * - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only enqueue work;
  *   they never synchronise with the host and never copy between host and device.
- * - All argument checks happen on the host BEFORE any HIP call; on any error nothing is enqueued and
+ * - All argument checks happen on the host before anything is enqueued; on any error nothing is launched and
  *   no output is written.  Errors are return codes only.  FEDRAG_ERR_DEVICE reports a failed launch.
  * - Supported: d_head in {64, 128}; n_q_heads % n_kv_heads == 0; token counts >= 0 (zero is legal).
  * - The library draws no randomness: keys (Phi's, permutations) come from the key holders

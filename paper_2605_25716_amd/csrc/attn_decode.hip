@@ -1,0 +1,307 @@
+// Decode-shaped partial attention (Section 4.1, per-node local computation) for 16-bit storage:
+// at most 16 query rows per (sequence, KV head) unit, i.e. the GQA group packed into one MFMA column tile.
+// HBM-bound: every K'/V' byte of the shard is read exactly once, nothing is reused, so the kernel is built
+// around keeping many full-row loads in flight per wave and no LDS traffic on the streaming path.
+//
+// One workgroup = one unit x one split of the shard's keys; its four waves take 32-key tiles round-robin.
+// Lane l of a wave: lr = l % 16, lq = l / 16.
+//   S^T tile (32 keys x 16 queries) = K'(32 x d) . Q'^T(d x 16): two 16-key MFMA tiles; this lane ends up with
+//   query lr and keys {16 mt + 4 lq + r}.  Those eight keys are also this lane's contraction slice of
+//   O^T(d x 16) += V'^T(d x 32) . P^T(32 x 16), whose d-rows are assigned d = DCH * i + j (tile j, row i) so
+//   that lane (i = lr) needs exactly the DCH contiguous elements [DCH*lr, DCH*lr + DCH) of each of its eight
+//   keys: full-row coalesced loads and an in-register 8 x DCH transpose.
+// P is split into two storage-type terms (hi + lo) so that the probabilities enter the second product with
+// ~16 significant bits; the matrix pipe is idle most of the time anyway.
+// Splits are normalised partials (O, lse) in the caller's workspace and are folded by the Section 4.1
+// aggregation kernel (merge.hip).
+#include "fedrag_device.h"
+#include "fedrag_host.h"
+
+namespace fedrag {
+
+// Transpose 8 rows of NC 16-bit elements: in[e] holds NC elements (NC/2 words), out[c] holds 8 (4 words).
+template <int NC>
+__device__ __forceinline__ void transpose_keys_b16(const uint32_t (&in)[8][NC / 2], u32x4_t (&out)[NC]) {
+#pragma unroll
+    for (int c2 = 0; c2 < NC / 2; ++c2) {
+#pragma unroll
+        for (int r2 = 0; r2 < 4; ++r2) {
+            const uint32_t a = in[2 * r2][c2];
+            const uint32_t b = in[2 * r2 + 1][c2];
+            out[2 * c2][r2] = __builtin_amdgcn_perm(b, a, 0x05040100u);      // {a.lo, b.lo}
+            out[2 * c2 + 1][r2] = __builtin_amdgcn_perm(b, a, 0x07060302u);  // {a.hi, b.hi}
+        }
+    }
+}
+
+template <class T, int D>
+struct DecTile {
+    typename T::vec8 k[2][D / 32];
+    uint32_t v[8][D / 32];
+};
+
+#ifndef FEDRAG_DEC_NBUF
+#define FEDRAG_DEC_NBUF 2   // register tile sets per wave
+#endif
+#ifndef FEDRAG_DEC_OCC
+#define FEDRAG_DEC_OCC 1    // workgroups per CU the register budget is sized for
+#endif
+#ifndef FEDRAG_DEC_AUX
+#define FEDRAG_DEC_AUX 2    // cache-policy bits of the streaming loads: non-temporal (K'/V' are read once)
+#endif
+
+template <class T, int D>
+__global__ __launch_bounds__(kDecThreads, FEDRAG_DEC_OCC) void decode_attn_kernel(const typename T::elem* __restrict__ Q,
+                                                                     const typename T::elem* __restrict__ K,
+                                                                     const typename T::elem* __restrict__ V, int R,
+                                                                     int64_t L, int n_splits, int64_t keys_per_split,
+                                                                     float scale_log2, float* __restrict__ O,
+                                                                     float* __restrict__ lse, int64_t total_rows) {
+    typedef typename T::elem elem;
+    typedef typename T::vec8 vec8;
+    typedef DecTile<T, D> Tile;
+    constexpr int KS = D / 32;   // contraction steps of the first product
+    constexpr int DCH = D / 16;  // elements per lane per key of V' (= number of 16-row tiles of O^T)
+    constexpr int NW = DCH / 2;  // 32-bit words of that
+    constexpr int ROWB = D * 2;  // bytes per row
+    constexpr int TILEB = kDecTile * ROWB;
+    constexpr int NBUF = FEDRAG_DEC_NBUF;
+    constexpr int AUX = FEDRAG_DEC_AUX;
+
+    __shared__ float sm_m[kDecWaves][16];
+    __shared__ float sm_l[kDecWaves][16];
+    __shared__ float sm_o[kDecWaves][16][D + 4];
+
+    const int tid = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);  // wave-uniform: keeps the tile loop scalar
+    const int lane = tid % kWave;
+    const int lr = lane % 16;
+    const int lq = lane / 16;
+    const int64_t unit = blockIdx.x / n_splits;
+    const int split = blockIdx.x % n_splits;
+    const int64_t k_begin = (int64_t)split * keys_per_split;
+    int64_t k_end = k_begin + keys_per_split;
+    if (k_end > L) k_end = L;
+
+    const elem* Qu = Q + unit * R * D;
+    const char* Kb = (const char*)(K + unit * L * D);
+    const char* Vb = (const char*)(V + unit * L * D);
+
+    // Q'^T operands: column lr (query), contraction slice 32 ks + 8 lq; padding queries are zero
+    vec8 qop[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks)
+        qop[ks] = (lr < R) ? *(const vec8*)(Qu + lr * D + ks * 32 + lq * 8) : zero_vec<vec8>();
+
+    f32x4_t acc_o[DCH];
+#pragma unroll
+    for (int i = 0; i < DCH; ++i) acc_o[i] = zero_vec<f32x4_t>();
+    float m_run = -INFINITY, l_run = 0.f;
+
+    // per-lane byte offsets inside a 32-key tile (the tile base is wave-uniform)
+    const uint32_t koff = (uint32_t)(lr * ROWB + lq * 16);
+    const uint32_t voff = (uint32_t)(lq * 4 * ROWB + lr * DCH * 2);
+
+    // Streaming loads go through buffer resources based at the split's first key: the address is
+    // (scalar resource base) + (scalar tile offset) + (per-lane 32-bit offset), one VGPR per lane in total.
+    const int64_t split_bytes = (k_end - k_begin) * ROWB;  // < 2^31, guaranteed by the split planner
+    const __amdgpu_buffer_rsrc_t rk =
+        __builtin_amdgcn_make_buffer_rsrc((void*)(Kb + k_begin * ROWB), 0, (int)split_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rv =
+        __builtin_amdgcn_make_buffer_rsrc((void*)(Vb + k_begin * ROWB), 0, (int)split_bytes, 0x00020000);
+    auto load_k = [&](int tile, Tile& t) {  // tile index inside the split; all 32 keys exist
+        const int soff = tile * TILEB;
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks)
+                t.k[mt][ks] = __builtin_bit_cast(
+                    vec8, __builtin_amdgcn_raw_buffer_load_b128(rk, (int)koff + mt * 16 * ROWB + ks * 64, soff, AUX));
+    };
+    auto load_v = [&](int tile, Tile& t) {
+        const int soff = tile * TILEB;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int off = (int)voff + ((e / 4) * 16 + (e % 4)) * ROWB;
+            if constexpr (NW == 4) {
+                const u32x4_t w = __builtin_amdgcn_raw_buffer_load_b128(rv, off, soff, AUX);
+                t.v[e][0] = w[0]; t.v[e][1] = w[1]; t.v[e][2] = w[2]; t.v[e][3] = w[3];
+            } else {
+                const u32x2_t w = __builtin_amdgcn_raw_buffer_load_b64(rv, off, soff, AUX);
+                t.v[e][0] = w[0]; t.v[e][1] = w[1];
+            }
+        }
+    };
+    auto load_clamped = [&](int64_t key0, Tile& t) {  // ragged last tile: rows past the end re-read row L-1
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt) {
+            int64_t key = key0 + mt * 16 + lr;
+            if (key >= L) key = L - 1;
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) t.k[mt][ks] = *(const vec8*)(Kb + key * ROWB + ks * 64 + lq * 16);
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            int64_t key = key0 + (e / 4) * 16 + lq * 4 + (e % 4);
+            if (key >= L) key = L - 1;
+            const uint32_t* p = (const uint32_t*)(Vb + key * ROWB + lr * DCH * 2);
+#pragma unroll
+            for (int w = 0; w < NW; ++w) t.v[e][w] = p[w];
+        }
+    };
+
+    // One 32-key tile.  `reload` refills the tile's registers for key `next0` as soon as each half has been
+    // consumed (K' after the first product, V' after the in-register transpose), so the loads fly behind the
+    // softmax, the second product and the other tile set's step.
+    auto step = [&](Tile& t, int64_t key0, bool masked, bool reload, int next_tile) {
+        f32x4_t s[2];
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt) {
+            s[mt] = zero_vec<f32x4_t>();
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) s[mt] = T::mfma16(t.k[mt][ks], qop[ks], s[mt]);
+        }
+        if (reload) load_k(next_tile, t);
+        float p[8];
+        float mx = -INFINITY;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            float v = s[e / 4][e % 4] * scale_log2;
+            if (masked) {
+                const int64_t key = key0 + (e / 4) * 16 + lq * 4 + (e % 4);
+                if (key >= k_end) v = -INFINITY;
+            }
+            p[e] = v;
+            mx = fmaxf(mx, v);
+        }
+        mx = fmaxf(mx, __shfl_xor(mx, 16));
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        const float m_new = fmaxf(m_run, mx);  // finite: the tile's first key exists
+        const float alpha = exp2_diff(m_run, m_new);
+        float psum = 0.f;
+        vec8 ph, pl;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const float pe = fast_exp2(p[e] - m_new);
+            psum += pe;
+            ph[e] = T::from_float(pe);
+            pl[e] = T::from_float(pe - T::to_float(ph[e]));
+        }
+        l_run = l_run * alpha + psum;
+        m_run = m_new;
+        // second product in two halves of the d-rows to keep the transposed operands short-lived
+        u32x4_t vt[DCH];
+        transpose_keys_b16<DCH>(t.v, vt);
+        if (reload) load_v(next_tile, t);
+#pragma unroll
+        for (int i = 0; i < DCH; ++i) {
+            acc_o[i] *= alpha;
+            const vec8 vop = __builtin_bit_cast(vec8, vt[i]);
+            acc_o[i] = T::mfma16(vop, ph, acc_o[i]);
+            acc_o[i] = T::mfma16(vop, pl, acc_o[i]);
+        }
+    };
+
+    // Wave w owns tiles w, w+4, ... of the split.  NBUF register tile sets form a ring: a set is refilled with
+    // the tile NBUF steps ahead as soon as it has been consumed.  In the steady-state loop every refill is
+    // unconditional, so the in-order load counter can be waited on precisely (oldest tile only).
+    {
+        const int64_t n_keys = k_end - k_begin;
+        const int n_full_all = (int)(n_keys / kDecTile);  // full tiles in the split
+        const int n_mine = (n_full_all > wave) ? (n_full_all - wave + kDecWaves - 1) / kDecWaves : 0;
+        auto tile_of = [&](int i) { return wave + i * kDecWaves; };  // i-th tile of this wave
+        auto tile_key = [&](int i) { return k_begin + (int64_t)tile_of(i) * kDecTile; };
+        Tile t[NBUF];
+#pragma unroll
+        for (int j = 0; j < NBUF; ++j)
+            if (j < n_mine) { load_k(tile_of(j), t[j]); load_v(tile_of(j), t[j]); }
+        int i = 0;
+        for (; i + 2 * NBUF <= n_mine; i += NBUF) {
+#pragma unroll
+            for (int j = 0; j < NBUF; ++j) step(t[j], tile_key(i + j), false, true, tile_of(i + j + NBUF));
+        }
+        // fewer than 2*NBUF tiles left: refills become conditional, then the ring drains
+#pragma unroll
+        for (int j = 0; j < NBUF; ++j) {
+            if (i + j < n_mine) {
+                if (i + j + NBUF < n_mine) step(t[j], tile_key(i + j), false, true, tile_of(i + j + NBUF));
+                else step(t[j], tile_key(i + j), false, false, 0);
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < NBUF; ++j)
+            if (i + NBUF + j < n_mine) step(t[j], tile_key(i + NBUF + j), false, false, 0);
+        // ragged tail of the split (fewer than 32 keys): the wave whose turn it is takes it
+        const int rem = (int)(n_keys % kDecTile);
+        if (rem > 0 && (n_full_all % kDecWaves) == wave) {
+            const int64_t key0 = k_begin + (int64_t)n_full_all * kDecTile;
+            load_clamped(key0, t[0]);
+            step(t[0], key0, true, false, 0);
+        }
+    }
+
+    // fold the four waves (Section 4.1 aggregation, in base 2)
+    float l_tot = l_run + __shfl_xor(l_run, 16);
+    l_tot += __shfl_xor(l_tot, 32);
+    if (lq == 0) {
+        sm_m[wave][lr] = m_run;
+        sm_l[wave][lr] = l_tot;
+    }
+    if (lr < R) {
+#pragma unroll
+        for (int i = 0; i < DCH; ++i)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) sm_o[wave][lr][DCH * (4 * lq + r) + i] = acc_o[i][r];
+    }
+    __syncthreads();
+    float* Oout = O + ((int64_t)split * total_rows + unit * R) * D;
+    float* Lout = lse + (int64_t)split * total_rows + unit * R;
+    for (int idx = tid; idx < R * D; idx += kDecThreads) {
+        const int n = idx / D;
+        const int d = idx % D;
+        float M = sm_m[0][n];
+#pragma unroll
+        for (int w = 1; w < kDecWaves; ++w) M = fmaxf(M, sm_m[w][n]);
+        float num = 0.f, den = 0.f;
+#pragma unroll
+        for (int w = 0; w < kDecWaves; ++w) {
+            const float a = exp2_diff(sm_m[w][n], M);
+            num = __builtin_fmaf(a, sm_o[w][n][d], num);
+            den = __builtin_fmaf(a, sm_l[w][n], den);
+        }
+        const bool any = den > 0.f;
+        Oout[n * D + d] = any ? num / den : 0.f;
+        if (d == 0) Lout[n] = any ? (M + fast_log2(den)) * kLn2 : -INFINITY;
+    }
+}
+
+template <class T, int D>
+static hipError_t launch_decode_t(const AttnProblem& p, hipStream_t stream) {
+    typedef typename T::elem elem;
+    const float scale_log2 = p.scale * kLog2e;
+    const int64_t rows = (int64_t)p.B * p.Hq * p.Lq;
+    const int splits = attn_kv_splits(p.B, p.Hq, p.Hkv, D, p.dtype, p.Lq, p.Lkv);
+    const int64_t per = decode_keys_per_split(p.Lkv, splits);
+    const int R = (int)((p.Hq / p.Hkv) * p.Lq);
+    const int64_t units = (int64_t)p.B * p.Hkv;
+    float* Odst = p.O;
+    float* Ldst = p.lse;
+    if (splits > 1) {
+        Odst = (float*)p.workspace;
+        Ldst = Odst + (size_t)splits * rows * D;
+    }
+    hipLaunchKernelGGL((decode_attn_kernel<T, D>), dim3((unsigned)(units * splits)), dim3(kDecThreads), 0, stream,
+                       (const elem*)p.Q, (const elem*)p.K, (const elem*)p.V, R, p.Lkv, splits, per, scale_log2, Odst,
+                       Ldst, rows);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || splits == 1) return e;
+    return launch_lse_merge(Odst, Ldst, splits, rows, D, p.O, p.lse, stream);
+}
+
+hipError_t launch_decode_attn(const AttnProblem& p, hipStream_t stream) {
+    if (p.dtype == FEDRAG_BF16)
+        return p.D == 128 ? launch_decode_t<BF16, 128>(p, stream) : launch_decode_t<BF16, 64>(p, stream);
+    return p.D == 128 ? launch_decode_t<F16, 128>(p, stream) : launch_decode_t<F16, 64>(p, stream);
+}
+
+}  // namespace fedrag

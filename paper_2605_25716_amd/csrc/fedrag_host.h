@@ -43,6 +43,15 @@ int attn_kv_splits(int B, int Hq, int Hkv, int D, int dtype, int64_t Lq, int64_t
 size_t attn_workspace_bytes(int B, int Hq, int Hkv, int D, int dtype, int64_t Lq, int64_t Lkv);
 hipError_t launch_partial_attn(const AttnProblem& p, hipStream_t stream);
 
+// decode kernel geometry (shared by the split planner and the kernel)
+constexpr int kDecWaves = 4;
+constexpr int kDecThreads = kDecWaves * 64;
+constexpr int kDecTile = 32;                      // keys per wave step
+constexpr int kDecStride = kDecWaves * kDecTile;  // keys per workgroup step
+int64_t decode_keys_per_split(int64_t Lkv, int n_splits);
+hipError_t launch_decode_attn(const AttnProblem& p, hipStream_t stream);   // 16-bit storage, G * L_q <= 16
+hipError_t launch_prefill_attn(const AttnProblem& p, hipStream_t stream);  // 16-bit storage, any L_q
+
 // Aggregation of S partials: O_parts [S, rows, D], lses [S, rows] -> O [rows, D], lse [rows].
 hipError_t launch_lse_merge(const float* O_parts, const float* lses, int S, int64_t rows, int D, float* O, float* lse,
                             hipStream_t stream);

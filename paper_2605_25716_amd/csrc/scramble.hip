@@ -15,7 +15,14 @@ namespace fedrag {
 
 constexpr int kScrWaves = 4;
 constexpr int kScrThreads = kScrWaves * kWave;
-constexpr int kScrPad = 8;  // elements of row padding in LDS (16 bytes: keeps 16-byte alignment, breaks bank stride)
+constexpr int kScrPad = 8;    // elements of row padding in LDS (16 bytes: keeps 16-byte alignment, breaks bank stride)
+constexpr int kScrRows = 32;  // rows per wave step (two 16-row MFMA column tiles)
+#ifndef FEDRAG_SCR_NBUF
+#define FEDRAG_SCR_NBUF 3     // register row-tile sets per wave (ring)
+#endif
+#ifndef FEDRAG_SCR_WGS
+#define FEDRAG_SCR_WGS 256    // workgroups to aim for over the whole launch (one per CU)
+#endif
 
 struct ScrambleJob {
     const void* X;
@@ -24,28 +31,36 @@ struct ScrambleJob {
 };
 
 // blockIdx.x = (bh * chunks + chunk); blockIdx.y selects the job (K or V).
+// Wave w of the workgroup owns the 32-row tiles w, w+4, ... of the chunk.  A ring of NBUF register tile sets
+// keeps NBUF-1 gathered tiles (8 KiB each) in flight per wave behind the LDS staging and the MFMAs; the gather
+// indices of a tile are fetched one step before its rows.
 template <class T, int D>
-__global__ __launch_bounds__(kScrThreads) void scramble_rows_kernel(ScrambleJob job0, ScrambleJob job1,
-                                                                    const int32_t* __restrict__ perm,
-                                                                    int64_t perm_batch_stride,  // 0 or L
-                                                                    int H, int G, int64_t L, int chunks,
-                                                                    int tiles_per_wave) {
+__global__ __launch_bounds__(kScrThreads, 1) void scramble_rows_kernel(ScrambleJob job0, ScrambleJob job1,
+                                                                       const int32_t* __restrict__ perm,
+                                                                       int64_t perm_batch_stride,  // 0 or L
+                                                                       int H, int G, int64_t L, int chunks,
+                                                                       int tiles_per_wave) {
     typedef typename T::elem elem;
     typedef typename T::vec8 vec8;
     typedef typename T::vec4 vec4;
     constexpr int LDP = D + kScrPad;
-    constexpr int CH = D / 8;          // 16-byte chunks per row
-    constexpr int RPI = kWave / CH;    // rows covered by one wave-wide 16-byte load
-    constexpr int NI = 16 / RPI;       // wave-wide loads per 16-row tile
-    constexpr int KS = D / 32;         // contraction steps
-    constexpr int MT = D / 16;         // output-column tiles
+    constexpr int CH = D / 8;              // 16-byte chunks per row
+    constexpr int RPI = kWave / CH;        // rows covered by one wave-wide 16-byte load
+    constexpr int NI = kScrRows / RPI;     // wave-wide loads per 32-row tile
+    constexpr int KS = D / 32;             // contraction steps
+    constexpr int MT = D / 16;             // output-column tiles
+    constexpr int NBUF = FEDRAG_SCR_NBUF;
+    constexpr int kPhiElems = D * LDP;
+    constexpr int kTileElems = kScrWaves * kScrRows * LDP;
+    constexpr int kLdsElems = kPhiElems > kTileElems ? kPhiElems : kTileElems;
 
-    __shared__ __attribute__((aligned(16))) elem phiT[D * LDP];             // Phi^T: [n][k]
-    __shared__ __attribute__((aligned(16))) elem tile[kScrWaves][16 * LDP];  // per-wave row tile
+    // Phi^T staging and the per-wave row tiles share one buffer: Phi^T is only needed until every wave has
+    // copied its MFMA operands into registers.
+    __shared__ __attribute__((aligned(16))) elem lds[kLdsElems];
 
     const ScrambleJob job = blockIdx.y == 0 ? job0 : job1;
     const int tid = threadIdx.x;
-    const int wave = tid / kWave;
+    const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);  // wave-uniform
     const int lane = tid % kWave;
     const int bh = blockIdx.x / chunks;
     const int chunk = blockIdx.x % chunks;
@@ -60,7 +75,7 @@ __global__ __launch_bounds__(kScrThreads) void scramble_rows_kernel(ScrambleJob 
             const int n0 = (c % CH) * 8;
             const vec8 v = *(const vec8*)(P + k * D + n0);
 #pragma unroll
-            for (int e = 0; e < 8; ++e) phiT[(n0 + e) * LDP + k] = v[e];
+            for (int e = 0; e < 8; ++e) lds[(n0 + e) * LDP + k] = v[e];
         }
     }
     __syncthreads();
@@ -73,73 +88,112 @@ __global__ __launch_bounds__(kScrThreads) void scramble_rows_kernel(ScrambleJob 
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks)
-            phi[mt][ks] = *(const vec8*)(&phiT[(mt * 16 + lr) * LDP + ks * 32 + lq * 8]);
+            phi[mt][ks] = *(const vec8*)(&lds[(mt * 16 + lr) * LDP + ks * 32 + lq * 8]);
+    __syncthreads();  // Phi^T is dead from here on; the buffer becomes the row tiles
 
     const elem* X = (const elem*)job.X + (int64_t)bh * L * D;
     elem* Y = (elem*)job.Y + (int64_t)bh * L * D;
     const int32_t* pm = perm ? perm + (int64_t)b * perm_batch_stride : nullptr;
-    elem* my = tile[wave];
+    elem* my = lds + wave * (kScrRows * LDP);
 
     const int ld_row = lane / CH;        // row within one wave-wide load
     const int ld_col = (lane % CH) * 8;  // element offset of this lane's 16 bytes
 
-    const int64_t chunk_row0 = (int64_t)chunk * tiles_per_wave * kScrWaves * 16;
+    const int64_t chunk_row0 = (int64_t)chunk * tiles_per_wave * kScrWaves * kScrRows;
+    auto tile_row0 = [&](int i) { return chunk_row0 + (int64_t)(i * kScrWaves + wave) * kScrRows; };
+    // tiles of this wave that start inside [0, L)
+    int n_mine = 0;
+    {
+        const int64_t first = tile_row0(0);
+        if (first < L) {
+            const int64_t left = (L - first + kScrWaves * kScrRows - 1) / (kScrWaves * kScrRows);
+            n_mine = left < tiles_per_wave ? (int)left : tiles_per_wave;
+        }
+    }
 
-    auto load_tile = [&](int64_t row0, vec8 (&buf)[NI]) {
+    // gather indices of a tile: lane l (< 32) holds the source row of tile row l; rows past the end re-read
+    // row L-1 (computed, never stored)
+    auto load_idx = [&](int i) -> int32_t {
+        int64_t j = tile_row0(i) + (lane % kScrRows);
+        if (j >= L) j = L - 1;
+        return pm ? pm[j] : (int32_t)j;
+    };
+    auto load_rows = [&](int32_t idx, vec8 (&buf)[NI]) {
 #pragma unroll
         for (int i = 0; i < NI; ++i) {
-            int64_t j = row0 + i * RPI + ld_row;
-            if (j >= L) j = L - 1;  // clamp: rows past the end are computed but never stored
-            const int64_t src = pm ? (int64_t)pm[j] : j;
-            buf[i] = *(const vec8*)(X + src * D + ld_col);
+            const int64_t src = __shfl(idx, i * RPI + ld_row);
+            buf[i] = __builtin_nontemporal_load((const vec8*)(X + src * D + ld_col));
         }
     };
 
-    vec8 cur[NI];
-    int64_t row0 = chunk_row0 + (int64_t)wave * 16;
-    if (row0 < L) load_tile(row0, cur);
-
-    for (int t = 0; t < tiles_per_wave; ++t, row0 += kScrWaves * 16) {
-        if (row0 >= L) break;  // wave-uniform
+    auto step = [&](vec8 (&buf)[NI], int i, bool reload, int32_t& idx_next) {
+        const int64_t row0 = tile_row0(i);
         // rows -> LDS tile
 #pragma unroll
-        for (int i = 0; i < NI; ++i) *(vec8*)(&my[(i * RPI + ld_row) * LDP + ld_col]) = cur[i];
+        for (int k = 0; k < NI; ++k) *(vec8*)(&my[(k * RPI + ld_row) * LDP + ld_col]) = buf[k];
         wave_lds_fence();
-        // prefetch the next tile of this wave while this one is multiplied
-        const int64_t next0 = row0 + kScrWaves * 16;
-        if (t + 1 < tiles_per_wave && next0 < L) load_tile(next0, cur);
-
-        // X^T operands: column = row lane%16 of the tile, contraction slice 32 ks + 8 (lane/16)
-        vec8 xop[KS];
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) xop[ks] = *(const vec8*)(&my[lr * LDP + ks * 32 + lq * 8]);
-
-        // Y^T tile (d x 16 rows) = Phi^T . X^T : lane holds row lane%16 of the tile, output columns 16 mt + 4 lq + r
-        f32x4_t acc[MT];
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-            acc[mt] = zero_vec<f32x4_t>();
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks) acc[mt] = T::mfma16(phi[mt][ks], xop[ks], acc[mt]);
+        if (reload) {  // refill this register set with the tile NBUF steps ahead, then fetch the indices after it
+            load_rows(idx_next, buf);
+            idx_next = load_idx(i + NBUF + 1);
         }
-        wave_lds_fence();  // all operand reads done before the tile is overwritten
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-            vec4 o;
+        for (int half = 0; half < 2; ++half) {
+            // X^T operands: column = row (16 half + lane%16) of the tile, contraction slice 32 ks + 8 (lane/16)
+            vec8 xop[KS];
 #pragma unroll
-            for (int r = 0; r < 4; ++r) o[r] = T::from_float(acc[mt][r]);
-            *(vec4*)(&my[lr * LDP + mt * 16 + lq * 4]) = o;
+            for (int ks = 0; ks < KS; ++ks)
+                xop[ks] = *(const vec8*)(&my[(half * 16 + lr) * LDP + ks * 32 + lq * 8]);
+            // Y^T tile (d x 16 rows) = Phi^T . X^T : lane holds tile row lane%16, output columns 16 mt + 4 lq + r
+            f32x4_t acc[MT];
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+                acc[mt] = zero_vec<f32x4_t>();
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) acc[mt] = T::mfma16(phi[mt][ks], xop[ks], acc[mt]);
+            }
+            // the 16 rows of this half are only read by the operand loads above (same wave, in order):
+            // overwrite them with the narrowed results
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+                vec4 o;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) o[r] = T::from_float(acc[mt][r]);
+                *(vec4*)(&my[(half * 16 + lr) * LDP + mt * 16 + lq * 4]) = o;
+            }
         }
         wave_lds_fence();
         // full-row stores
 #pragma unroll
-        for (int i = 0; i < NI; ++i) {
-            const int64_t j = row0 + i * RPI + ld_row;
-            const vec8 v = *(const vec8*)(&my[(i * RPI + ld_row) * LDP + ld_col]);
-            if (j < L) *(vec8*)(Y + j * D + ld_col) = v;
+        for (int k = 0; k < NI; ++k) {
+            const int64_t j = row0 + k * RPI + ld_row;
+            const vec8 v = *(const vec8*)(&my[(k * RPI + ld_row) * LDP + ld_col]);
+            if (j < L) __builtin_nontemporal_store(v, (vec8*)(Y + j * D + ld_col));
         }
         wave_lds_fence();  // reads of the output tile done before the next tile's rows land
+    };
+
+    vec8 buf[NBUF][NI];
+    int32_t idx_next = 0;
+#pragma unroll
+    for (int j = 0; j < NBUF; ++j)
+        if (j < n_mine) load_rows(load_idx(j), buf[j]);
+    if (NBUF < n_mine) idx_next = load_idx(NBUF);
+    int i = 0;
+    // steady state: tiles i+NBUF .. exist for every set, index prefetch may run one tile past the end (clamped)
+    for (; i + 2 * NBUF <= n_mine; i += NBUF) {
+#pragma unroll
+        for (int j = 0; j < NBUF; ++j) step(buf[j], i + j, true, idx_next);
     }
+#pragma unroll
+    for (int j = 0; j < NBUF; ++j) {
+        if (i + j < n_mine) {
+            if (i + j + NBUF < n_mine) step(buf[j], i + j, true, idx_next);
+            else step(buf[j], i + j, false, idx_next);
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < NBUF; ++j)
+        if (i + NBUF + j < n_mine) step(buf[j], i + NBUF + j, false, idx_next);
 }
 
 // fp32 rows times fp32 matrix with plain FMAs (fp32 storage path of Enc, and Dec for every storage type).
@@ -213,14 +267,14 @@ static int ceil_div_i64(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
 
 template <class T, int D>
 static hipError_t launch_scramble16(const RowsJob& j, hipStream_t stream) {
-    const int64_t tiles64 = (j.L + 63) / 64;  // 64 rows = one pass of the 4 waves
-    // aim at ~4 workgroups per CU over the whole launch so that Phi staging is amortised
-    const int64_t want_wgs = 1024;
-    const int64_t total = tiles64 * j.BH * j.n_jobs;
-    int tpw = (int)((total + want_wgs - 1) / want_wgs);
+    const int64_t rows_per_pass = kScrWaves * kScrRows;  // rows one workgroup covers per ring step
+    const int64_t passes = (j.L + rows_per_pass - 1) / rows_per_pass;
+    // about one workgroup per CU over the whole launch: long streams per wave, Phi staged once per workgroup
+    const int64_t total = passes * j.BH * j.n_jobs;
+    int tpw = (int)((total + FEDRAG_SCR_WGS - 1) / FEDRAG_SCR_WGS);
     if (tpw < 1) tpw = 1;
-    if (tpw > 64) tpw = 64;
-    const int chunks = ceil_div_i64(tiles64, tpw);
+    if (tpw > 4096) tpw = 4096;
+    const int chunks = ceil_div_i64(passes, tpw);
     dim3 grid((unsigned)(j.BH * chunks), (unsigned)j.n_jobs);
     ScrambleJob a{j.X[0], j.Phi[0], j.Y[0]}, b{j.X[1], j.Phi[1], j.Y[1]};
     hipLaunchKernelGGL((scramble_rows_kernel<T, D>), grid, dim3(kScrThreads), 0, stream, a, b, j.perm,
