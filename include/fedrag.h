@@ -89,7 +89,7 @@ fedrag_status fedrag_scramble_q(const fedrag_shape* shape, int64_t L_q, const vo
  *     lse[b,h,i]      = ln sum_t exp( <Qs[b,h,i], Ks[b,g,t]> * softmax_scale )  ( = ln [w_i]_l )
  * No mask: every query row sees every key of the shard.  The normalisation factor is carried as its
  * natural logarithm so that outlier logits cannot overflow; softmax_scale is applied in fp32 to the
- * accumulated dot product (pass 1/sqrt(d)).
+ * accumulated dot product (pass 1/sqrt(d)); it must be finite and > 0 (FEDRAG_ERR_SHAPE otherwise).
  * Qs : [B,Hq,L_q,d], Ks/Vs : [B,Hkv,L_kv,d] in shape->dtype.  O_part : fp32 [B,Hq,L_q,d], lse : fp32 [B,Hq,L_q].
  * L_kv == 0 gives O_part = 0 and lse = -inf.
  * workspace : device scratch of at least fedrag_partial_attn_workspace_bytes(shape, L_q, L_kv) bytes

@@ -1,57 +1,62 @@
 // Prefill-shaped partial attention (Section 4.1, per-node local computation) for 16-bit storage: many query rows
-// per head against one KV shard, non-causal.  MFMA-bound: K'/V' tiles are staged in LDS and shared by the
-// workgroup's waves; both products are computed transposed (S^T = K' Q'^T, O^T = V'^T P^T) so that the fp32 score
-// tile already sits in the lane layout the second product wants for P^T.
+// per head against one KV shard, non-causal.  MFMA-bound, with the softmax VALU work a close second, so the kernel
+// is organised to let the two overlap:
+//   * one workgroup = 8 waves (two per SIMD) x 32 query rows = 256 query rows of one (sequence, query head);
+//     while one wave of a SIMD is in its MFMA phase the other runs its softmax;
+//   * K'/V' tiles of 64 keys are shared by the 8 waves through a double-buffered LDS stage (one barrier per
+//     tile); the next tile's global loads fly during the current tile's arithmetic;
+//   * both products are computed transposed, S^T = K' Q'^T and O^T = V'^T P^T (32x32x16 MFMA), so the fp32
+//     score tile already sits in the lane layout the second product wants for P^T: probabilities never cross
+//     lanes.  K' operands are plain 16-byte LDS reads; V'^T operands come from the row-major V' tile through
+//     the transposing LDS read (ds_read_b64_tr_b16), so V' is never transposed in memory or in registers;
+//   * workgroups that share a KV head are placed on the same XCD (shared L2).
 #include "fedrag_device.h"
 #include "fedrag_host.h"
 
 namespace fedrag {
 
-template <int NC>
-__device__ __forceinline__ void transpose_keys_b16(const uint32_t (&in)[8][NC / 2], u32x4_t (&out)[NC]) {
-#pragma unroll
-    for (int c2 = 0; c2 < NC / 2; ++c2) {
-#pragma unroll
-        for (int r2 = 0; r2 < 4; ++r2) {
-            const uint32_t a = in[2 * r2][c2];
-            const uint32_t b = in[2 * r2 + 1][c2];
-            out[2 * c2][r2] = __builtin_amdgcn_perm(b, a, 0x05040100u);      // {a.lo, b.lo}
-            out[2 * c2 + 1][r2] = __builtin_amdgcn_perm(b, a, 0x07060302u);  // {a.hi, b.hi}
-        }
-    }
+constexpr int kPreWaves = 8;
+constexpr int kPreThreads = kPreWaves * kWave;
+constexpr int kPreQ = 32;                     // query rows per wave (one 32-wide MFMA column tile)
+constexpr int kPreQTile = kPreWaves * kPreQ;  // query rows per workgroup
+constexpr int kPreK = 64;                     // keys per LDS tile
+constexpr int kPreKPad = 16;                  // bytes of row padding, K' tile: 16-byte operand reads, 32 rows
+constexpr int kPreVPad = 64;                  // bytes of row padding, V' tile: transposing reads, 4 rows x 64 bytes
+
+typedef short s16x4_t __attribute__((ext_vector_type(4)));
+
+// Transposing LDS read: within each group of 16 lanes, lane j receives element (j % 4) of the 8 bytes addressed
+// by lane 4 e + j / 4, for e = 0..3.  With lane s of the group pointing at row (s / 4), columns 4 (s % 4)..+4 of
+// a row-major 4 x 16 block, lane j gets column j of the block, rows 0..3.
+__device__ __forceinline__ u32x2_t lds_read_tr16(const char* p) {
+    const s16x4_t v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4_t __attribute__((address_space(3)))*)p);
+    return __builtin_bit_cast(u32x2_t, v);
 }
 
-constexpr int kPreWaves = 4;
-constexpr int kPreThreads = kPreWaves * kWave;
-constexpr int kPreQ = 32;                    // query rows per wave (one 32-wide MFMA column tile)
-constexpr int kPreQTile = kPreWaves * kPreQ; // query rows per workgroup
-constexpr int kPreK = 64;                    // keys per LDS tile
-constexpr int kPrePad = 8;
+template <int D>
+constexpr int prefill_lds_bytes() {
+    return 2 * kPreK * (D * 2 + kPreKPad) + 2 * kPreK * (D * 2 + kPreVPad);
+}
 
-// One workgroup = 128 query rows of one (sequence, query head) against the whole shard.
-// Lane l: li = l % 32, lh = l / 32.  32x32x16 MFMA:
-//   S^T(64 keys x 32 q) = K'tile . Q'^T : two 32-key tiles x (d/16) steps; lane gets query li and, per tile, keys
-//   8*(r/4) + 4*lh + r%4 (r = 0..15).  Registers r in [8kk', 8kk'+8) are this lane's contraction slice of the
-//   16-key step kk = 2 mt + kk' of O^T(d x 32 q) += V'^T . P^T, whose d-rows are assigned d = DCH*i + mt'
-//   (DCH = d/32) so lane (i = li) reads DCH contiguous elements of each of its 8 keys from the LDS tile and
-//   transposes them in registers.
 template <class T, int D>
-__global__ __launch_bounds__(kPreThreads) void prefill_attn_kernel(const typename T::elem* __restrict__ Q,
-                                                                   const typename T::elem* __restrict__ K,
-                                                                   const typename T::elem* __restrict__ V, int Hq,
-                                                                   int Hkv, int64_t Lq, int64_t L, int q_tiles,
-                                                                   int n_units, float scale_log2,
-                                                                   float* __restrict__ O, float* __restrict__ lse) {
+__global__ __launch_bounds__(kPreThreads, 1) void prefill_attn_kernel(const typename T::elem* __restrict__ Q,
+                                                                      const typename T::elem* __restrict__ K,
+                                                                      const typename T::elem* __restrict__ V, int Hq,
+                                                                      int Hkv, int64_t Lq, int64_t L, int q_tiles,
+                                                                      int n_units, float scale_log2,
+                                                                      float* __restrict__ O, float* __restrict__ lse) {
     typedef typename T::elem elem;
     typedef typename T::vec8 vec8;
-    constexpr int LDP = D + kPrePad;
-    constexpr int KS = D / 16;   // contraction steps of S^T
-    constexpr int DCH = D / 32;  // V' elements per lane per key = 32-row tiles of O^T
-    constexpr int CH = D / 8;    // 16-byte chunks per row
-    constexpr int LPT = (kPreK * CH) / kPreThreads;  // 16-byte loads per thread per tile (K or V)
+    constexpr int KROW = D * 2 + kPreKPad;  // bytes per K' tile row in LDS
+    constexpr int VROW = D * 2 + kPreVPad;  // bytes per V' tile row in LDS
+    constexpr int KS = D / 16;              // contraction steps of S^T
+    constexpr int MT = D / 32;              // 32-row tiles of O^T
+    constexpr int CH = D / 8;               // 16-byte chunks per row
+    constexpr int LPT = (kPreK * CH) / kPreThreads;  // 16-byte loads per thread per tile (K' and V' each)
 
-    __shared__ __attribute__((aligned(16))) elem ks_[kPreK * LDP];
-    __shared__ __attribute__((aligned(16))) elem vs_[kPreK * LDP];
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    char* const ks_ = smem;                      // [2][64][KROW]
+    char* const vs_ = smem + 2 * kPreK * KROW;   // [2][64][VROW]
 
     // XCD-aware placement: consecutive workgroup ids are dealt round-robin to the 8 XCDs (one L2 each);
     // give every XCD whole (sequence, KV head) units so that the workgroups sharing K'/V' share an L2.
@@ -82,15 +87,16 @@ __global__ __launch_bounds__(kPreThreads) void prefill_attn_kernel(const typenam
 
     const int64_t q_row = (int64_t)qt * kPreQTile + wave * kPreQ + li;  // this lane's query row
     const int64_t q_ld = q_row < Lq ? q_row : Lq - 1;
-    vec8 qop[KS];
+    vec8 qop[KS];  // Q'^T operands: column li, contraction slice 16 ks + 8 lh
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) qop[ks] = *(const vec8*)(Qh + q_ld * D + ks * 16 + lh * 8);
 
-    f32x16_t acc_o[DCH];
+    f32x16_t acc_o[MT];
 #pragma unroll
-    for (int i = 0; i < DCH; ++i) acc_o[i] = zero_vec<f32x16_t>();
+    for (int i = 0; i < MT; ++i) acc_o[i] = zero_vec<f32x16_t>();
     float m_run = -INFINITY, l_run = 0.f;
 
+    // global -> registers -> LDS staging of the next tile
     vec8 kreg[LPT], vreg[LPT];
     auto load_tile = [&](int64_t key0) {
 #pragma unroll
@@ -102,122 +108,133 @@ __global__ __launch_bounds__(kPreThreads) void prefill_attn_kernel(const typenam
             vreg[i] = *(const vec8*)(Vg + key * D + (c % CH) * 8);
         }
     };
-    auto store_tile = [&]() {
+    auto store_tile = [&](int buf) {
 #pragma unroll
         for (int i = 0; i < LPT; ++i) {
             const int c = i * kPreThreads + tid;
-            *(vec8*)(&ks_[(c / CH) * LDP + (c % CH) * 8]) = kreg[i];
-            *(vec8*)(&vs_[(c / CH) * LDP + (c % CH) * 8]) = vreg[i];
+            *(vec8*)(ks_ + (buf * kPreK + c / CH) * KROW + (c % CH) * 16) = kreg[i];
+            *(vec8*)(vs_ + (buf * kPreK + c / CH) * VROW + (c % CH) * 16) = vreg[i];
         }
     };
 
-    if (L > 0) load_tile(0);
-    for (int64_t key0 = 0; key0 < L; key0 += kPreK) {
-        __syncthreads();  // everyone finished reading the previous tile
-        store_tile();
-        __syncthreads();
-        if (key0 + kPreK < L) load_tile(key0 + kPreK);
+    // per-lane LDS offsets
+    const int k_rd = li * KROW + lh * 16;  // K' operand: row 32 mt + li, bytes 32 ks + 16 lh
+    // V'^T operand through the transposing read: 16-lane group gq covers d-rows 16 (gq % 2) .. +16 of the 32-row
+    // tile; lane s of the group points at key row (4 lh + s / 4) (+8 for the second read), columns 4 (s % 4)..+4
+    const int s16 = lane % 16;
+    const int gq = lane / 16;
+    const int v_rd = (4 * lh + s16 / 4) * VROW + ((gq % 2) * 16 + 4 * (s16 % 4)) * 2;
 
-        // S^T for this wave's 32 queries
+    if (L > 0) {
+        load_tile(0);
+        store_tile(0);
+    }
+    __syncthreads();
+    const int n_tiles = (int)((L + kPreK - 1) / kPreK);
+    for (int t = 0; t < n_tiles; ++t) {
+        const int buf = t & 1;
+        const int64_t key0 = (int64_t)t * kPreK;
+        if (t + 1 < n_tiles) load_tile(key0 + kPreK);
+        const char* kt = ks_ + buf * kPreK * KROW;
+        const char* vt = vs_ + buf * kPreK * VROW;
+
+        // S^T (64 keys x 32 queries) for this wave: lane gets query li and, per 32-key tile mt, keys
+        // 8 (r / 4) + 4 lh + r % 4, r = 0..15
         f32x16_t s[2];
 #pragma unroll
         for (int mt = 0; mt < 2; ++mt) {
             s[mt] = zero_vec<f32x16_t>();
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
-                const vec8 kop = *(const vec8*)(&ks_[(mt * 32 + li) * LDP + ks * 16 + lh * 8]);
+                const vec8 kop = *(const vec8*)(kt + mt * 32 * KROW + k_rd + ks * 32);
                 s[mt] = T::mfma32(kop, qop[ks], s[mt]);
             }
         }
-        // online softmax over this lane's 32 keys and its partner lane's 32 keys
-        const bool tail = key0 + kPreK > L;
-        float mx = -INFINITY;
+        // online softmax over this lane's 32 keys and its partner lane's 32 keys (base-2 domain)
+        if (key0 + kPreK > L) {  // ragged last tile
+#pragma unroll
+            for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int64_t key = key0 + mt * 32 + 8 * (r / 4) + 4 * lh + (r % 4);
+                    if (key >= L) s[mt][r] = -INFINITY;
+                }
+        }
+        float mx = s[0][0];
 #pragma unroll
         for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                float v = s[mt][r] * scale_log2;
-                if (tail) {
-                    const int64_t key = key0 + mt * 32 + 8 * (r / 4) + 4 * lh + (r % 4);
-                    if (key >= L) v = -INFINITY;
-                }
-                s[mt][r] = v;
-                mx = fmaxf(mx, v);
-            }
+            for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[mt][r]);
         mx = fmaxf(mx, __shfl_xor(mx, 32));
-        const float m_new = fmaxf(m_run, mx);
+        const float m_new = fmaxf(m_run, mx * scale_log2);  // scale > 0: max commutes with the scaling
         const float alpha = exp2_diff(m_run, m_new);
         float psum = 0.f;
-        vec8 pop[4];
+        vec8 pop[4];  // P^T operands: step kk = 2 mt + r / 8 holds registers r = 8 (kk % 2) .. +8
 #pragma unroll
         for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const float pe = fast_exp2(s[mt][r] - m_new);
+                const float pe = fast_exp2(__builtin_fmaf(s[mt][r], scale_log2, -m_new));
                 psum += pe;
                 pop[2 * mt + r / 8][r % 8] = T::from_float(pe);
             }
         l_run = l_run * alpha + psum;
         m_run = m_new;
-        if (alpha != 1.0f) {
+        if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {  // wave-uniform: skip when no row's maximum moved
 #pragma unroll
-            for (int i = 0; i < DCH; ++i) acc_o[i] *= alpha;
+            for (int i = 0; i < MT; ++i) acc_o[i] *= alpha;
         }
-        // O^T += V'^T P^T, 16 keys per step
+        // O^T += V'^T P^T, 16 keys per step: contraction element e <-> key 16 kk + 8 (e / 4) + 4 lh + e % 4
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
-            uint32_t vin[8][DCH / 2];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const int key = kk * 16 + 8 * (e / 4) + 4 * lh + (e % 4);
-                const uint32_t* p = (const uint32_t*)(&vs_[key * LDP + li * DCH]);
-                if constexpr (DCH == 4) {
-                    const u32x2_t w = *(const u32x2_t*)p;
-                    vin[e][0] = w[0]; vin[e][1] = w[1];
-                } else {
-                    vin[e][0] = *p;
-                }
+            for (int i = 0; i < MT; ++i) {
+                const char* p = vt + kk * 16 * VROW + v_rd + i * 64;
+                const u32x2_t lo = lds_read_tr16(p);
+                const u32x2_t hi = lds_read_tr16(p + 8 * VROW);
+                u32x4_t w;
+                w[0] = lo[0]; w[1] = lo[1]; w[2] = hi[0]; w[3] = hi[1];
+                acc_o[i] = T::mfma32(__builtin_bit_cast(vec8, w), pop[kk], acc_o[i]);
             }
-            u32x4_t vt[DCH];
-            transpose_keys_b16<DCH>(vin, vt);
-#pragma unroll
-            for (int i = 0; i < DCH; ++i)
-                acc_o[i] = T::mfma32(__builtin_bit_cast(vec8, vt[i]), pop[kk], acc_o[i]);
         }
+        if (t + 1 < n_tiles) store_tile(buf ^ 1);
+        __syncthreads();
     }
 
-    // epilogue: lane holds query li, rows d = DCH * (8*(r/4) + 4*lh + r%4) + i of O^T
-    float l_tot = l_run + __shfl_xor(l_run, 32);
+    // epilogue: lane holds query li and rows d = 32 i + 8 (r / 4) + 4 lh + r % 4 of O^T
+    const float l_tot = l_run + __shfl_xor(l_run, 32);
     const float inv = (l_tot > 0.f) ? 1.0f / l_tot : 0.f;
     if (q_row < Lq) {
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int row = 8 * (r / 4) + 4 * lh + (r % 4);
-            if constexpr (DCH == 4) {
+        for (int i = 0; i < MT; ++i)
+#pragma unroll
+            for (int r4 = 0; r4 < 4; ++r4) {
                 f32x4_t o;
 #pragma unroll
-                for (int i = 0; i < 4; ++i) o[i] = acc_o[i][r] * inv;
-                *(f32x4_t*)(Oh + q_row * D + row * 4) = o;
-            } else {
-                Oh[q_row * D + row * 2 + 0] = acc_o[0][r] * inv;
-                Oh[q_row * D + row * 2 + 1] = acc_o[1][r] * inv;
+                for (int r = 0; r < 4; ++r) o[r] = acc_o[i][4 * r4 + r] * inv;
+                *(f32x4_t*)(Oh + q_row * D + 32 * i + 8 * r4 + 4 * lh) = o;
             }
-        }
         if (lh == 0) Lh[q_row] = (l_tot > 0.f) ? (m_run + fast_log2(l_tot)) * kLn2 : -INFINITY;
     }
 }
 
-
 template <class T, int D>
 static hipError_t launch_prefill_t(const AttnProblem& p, hipStream_t stream) {
     typedef typename T::elem elem;
+    static bool configured = false;  // opt in to more than 64 KiB of LDS once per kernel instantiation
+    if (!configured) {
+        hipError_t e = hipFuncSetAttribute((const void*)prefill_attn_kernel<T, D>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, prefill_lds_bytes<D>());
+        if (e != hipSuccess) return e;
+        configured = true;
+    }
     const float scale_log2 = p.scale * kLog2e;
     const int q_tiles = (int)((p.Lq + kPreQTile - 1) / kPreQTile);
     const int n_units = p.B * p.Hkv;
     const int per_unit = (p.Hq / p.Hkv) * q_tiles;
     const int64_t grid = (int64_t)8 * ((n_units + 7) / 8) * per_unit;
-    hipLaunchKernelGGL((prefill_attn_kernel<T, D>), dim3((unsigned)grid), dim3(kPreThreads), 0, stream,
-                       (const elem*)p.Q, (const elem*)p.K, (const elem*)p.V, p.Hq, p.Hkv, p.Lq, p.Lkv, q_tiles,
+    hipLaunchKernelGGL((prefill_attn_kernel<T, D>), dim3((unsigned)grid), dim3(kPreThreads), prefill_lds_bytes<D>(),
+                       stream, (const elem*)p.Q, (const elem*)p.K, (const elem*)p.V, p.Hq, p.Hkv, p.Lq, p.Lkv, q_tiles,
                        n_units, scale_log2, p.O, p.lse);
     return hipGetLastError();
 }

@@ -124,7 +124,7 @@ fedrag_status fedrag_partial_attn(const fedrag_shape* shape, int64_t L_q, int64_
     if (!tensor_elems(shape->batch, shape->n_q_heads, L_q, shape->d_head, &nq) ||
         !tensor_elems(shape->batch, shape->n_kv_heads, L_kv, shape->d_head, &nk))
         return FEDRAG_ERR_SHAPE;
-    if (!(softmax_scale == softmax_scale) || softmax_scale - softmax_scale != 0.0f) return FEDRAG_ERR_SHAPE;
+    if (!(softmax_scale > 0.0f) || softmax_scale - softmax_scale != 0.0f) return FEDRAG_ERR_SHAPE;  // finite, > 0
     if (!aligned16(Qs) || !aligned16(Ks) || !aligned16(Vs) || !aligned16(O_part) ||
         (reinterpret_cast<uintptr_t>(lse) & 3u) || !aligned16(workspace))
         return FEDRAG_ERR_ALIAS;

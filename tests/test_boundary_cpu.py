@@ -98,8 +98,9 @@ def test_partial_attn_validation_and_workspace(lib):
     assert f(*a) == fb.ERR_NULL
     a = base(); a[2] = -5
     assert f(*a) == fb.ERR_SHAPE
-    a = base(); a[6] = ctypes.c_float(float("nan"))
-    assert f(*a) == fb.ERR_SHAPE
+    for bad_scale in (float("nan"), float("inf"), 0.0, -0.1):
+        a = base(); a[6] = ctypes.c_float(bad_scale)
+        assert f(*a) == fb.ERR_SHAPE
     a = base(); a[3] = P(A + 8)
     assert f(*a) == fb.ERR_ALIAS
     # workspace query: prefill-shaped and fp32 problems need none; bad shapes report 0
