@@ -22,6 +22,9 @@ constexpr int kPreQTile = kPreWaves * kPreQ;  // query rows per workgroup
 constexpr int kPreK = 64;                     // keys per LDS tile
 constexpr int kPreKPad = 16;                  // bytes of row padding, K' tile: 16-byte operand reads, 32 rows
 constexpr int kPreVPad = 64;                  // bytes of row padding, V' tile: transposing reads, 4 rows x 64 bytes
+#ifndef FEDRAG_PRE_PRIO
+#define FEDRAG_PRE_PRIO 1  // 0: equal wave priorities; 1: first four waves high; 2: raised during MFMA phases
+#endif
 
 typedef short s16x4_t __attribute__((ext_vector_type(4)));
 
@@ -102,10 +105,10 @@ __global__ __launch_bounds__(kPreThreads, 1) void prefill_attn_kernel(const type
 #pragma unroll
         for (int i = 0; i < LPT; ++i) {
             const int c = i * kPreThreads + tid;
-            int64_t key = key0 + c / CH;
-            if (key >= L) key = L - 1;
-            kreg[i] = *(const vec8*)(Kg + key * D + (c % CH) * 8);
-            vreg[i] = *(const vec8*)(Vg + key * D + (c % CH) * 8);
+            int key = (int)key0 + c / CH;  // L fits in 31 bits (checked by the caller)
+            if (key >= (int)L) key = (int)L - 1;
+            kreg[i] = *(const vec8*)(Kg + (int64_t)key * D + (c % CH) * 8);
+            vreg[i] = *(const vec8*)(Vg + (int64_t)key * D + (c % CH) * 8);
         }
     };
     auto store_tile = [&](int buf) {
@@ -125,6 +128,12 @@ __global__ __launch_bounds__(kPreThreads, 1) void prefill_attn_kernel(const type
     const int gq = lane / 16;
     const int v_rd = (4 * lh + s16 / 4) * VROW + ((gq % 2) * 16 + 4 * (s16 % 4)) * 2;
 
+#if FEDRAG_PRE_PRIO == 1
+    // The two waves that share a SIMD run identical instruction streams and leave every barrier together; giving
+    // one of them priority makes it win each contested pipe, so the pair falls into complementary phases
+    // (one in its MFMA phase while the other is in its softmax) instead of contending in lockstep.
+    if (wave < kPreWaves / 2) __builtin_amdgcn_s_setprio(2);
+#endif
     if (L > 0) {
         load_tile(0);
         store_tile(0);
@@ -139,25 +148,55 @@ __global__ __launch_bounds__(kPreThreads, 1) void prefill_attn_kernel(const type
         const char* vt = vs_ + buf * kPreK * VROW;
 
         // S^T (64 keys x 32 queries) for this wave: lane gets query li and, per 32-key tile mt, keys
-        // 8 (r / 4) + 4 lh + r % 4, r = 0..15
+        // 8 (r / 4) + 4 lh + r % 4, r = 0..15.  All K' operands are requested before the first MFMA so that the
+        // LDS latency is paid once; the two 32-key tiles form two independent accumulation chains.
         f32x16_t s[2];
+        {
+            vec8 kop[2][KS];
 #pragma unroll
-        for (int mt = 0; mt < 2; ++mt) {
-            s[mt] = zero_vec<f32x16_t>();
+            for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks)
+                    kop[mt][ks] = *(const vec8*)(kt + mt * 32 * KROW + k_rd + ks * 32);
+            __builtin_amdgcn_sched_barrier(0);  // keep the reads ahead of the MFMAs
+#if FEDRAG_PRE_PRIO == 2
+            __builtin_amdgcn_s_setprio(2);
+#endif
+            s[0] = zero_vec<f32x16_t>();
+            s[1] = zero_vec<f32x16_t>();
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
-                const vec8 kop = *(const vec8*)(kt + mt * 32 * KROW + k_rd + ks * 32);
-                s[mt] = T::mfma32(kop, qop[ks], s[mt]);
+                s[0] = T::mfma32(kop[0][ks], qop[ks], s[0]);
+                s[1] = T::mfma32(kop[1][ks], qop[ks], s[1]);
             }
+#if FEDRAG_PRE_PRIO == 2
+            __builtin_amdgcn_s_setprio(0);
+#endif
         }
+        // V'^T operands of the first two 16-key steps: requested now, consumed after the softmax
+        auto read_vop = [&](int kk, int i) -> vec8 {
+            const char* p = vt + kk * 16 * VROW + v_rd + i * 64;
+            const u32x2_t lo = lds_read_tr16(p);
+            const u32x2_t hi = lds_read_tr16(p + 8 * VROW);
+            u32x4_t w;
+            w[0] = lo[0]; w[1] = lo[1]; w[2] = hi[0]; w[3] = hi[1];
+            return __builtin_bit_cast(vec8, w);
+        };
+        vec8 vop_a[2][MT];
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+            for (int i = 0; i < MT; ++i) vop_a[kk][i] = read_vop(kk, i);
+        __builtin_amdgcn_sched_barrier(0);  // requested before the softmax starts
+
         // online softmax over this lane's 32 keys and its partner lane's 32 keys (base-2 domain)
         if (key0 + kPreK > L) {  // ragged last tile
 #pragma unroll
             for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
-                    const int64_t key = key0 + mt * 32 + 8 * (r / 4) + 4 * lh + (r % 4);
-                    if (key >= L) s[mt][r] = -INFINITY;
+                    const int key = (int)key0 + mt * 32 + 8 * (r / 4) + 4 * lh + (r % 4);
+                    if (key >= (int)L) s[mt][r] = -INFINITY;
                 }
         }
         float mx = s[0][0];
@@ -180,23 +219,32 @@ __global__ __launch_bounds__(kPreThreads, 1) void prefill_attn_kernel(const type
             }
         l_run = l_run * alpha + psum;
         m_run = m_new;
+        // second half of the V'^T operands: in flight behind the first eight MFMAs
+        vec8 vop_b[2][MT];
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+            for (int i = 0; i < MT; ++i) vop_b[kk][i] = read_vop(2 + kk, i);
+        __builtin_amdgcn_sched_barrier(0);
         if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {  // wave-uniform: skip when no row's maximum moved
 #pragma unroll
             for (int i = 0; i < MT; ++i) acc_o[i] *= alpha;
         }
         // O^T += V'^T P^T, 16 keys per step: contraction element e <-> key 16 kk + 8 (e / 4) + 4 lh + e % 4
+#if FEDRAG_PRE_PRIO == 2
+        __builtin_amdgcn_s_setprio(2);
+#endif
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
+        for (int kk = 0; kk < 2; ++kk)
 #pragma unroll
-            for (int i = 0; i < MT; ++i) {
-                const char* p = vt + kk * 16 * VROW + v_rd + i * 64;
-                const u32x2_t lo = lds_read_tr16(p);
-                const u32x2_t hi = lds_read_tr16(p + 8 * VROW);
-                u32x4_t w;
-                w[0] = lo[0]; w[1] = lo[1]; w[2] = hi[0]; w[3] = hi[1];
-                acc_o[i] = T::mfma32(__builtin_bit_cast(vec8, w), pop[kk], acc_o[i]);
-            }
-        }
+            for (int i = 0; i < MT; ++i) acc_o[i] = T::mfma32(vop_a[kk][i], pop[kk], acc_o[i]);
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+            for (int i = 0; i < MT; ++i) acc_o[i] = T::mfma32(vop_b[kk][i], pop[2 + kk], acc_o[i]);
+#if FEDRAG_PRE_PRIO == 2
+        __builtin_amdgcn_s_setprio(0);
+#endif
         if (t + 1 < n_tiles) store_tile(buf ^ 1);
         __syncthreads();
     }

@@ -117,7 +117,7 @@ fedrag_status fedrag_partial_attn(const fedrag_shape* shape, int64_t L_q, int64_
                                   void* workspace, size_t workspace_bytes, void* stream) {
     fedrag_status st = check_shape(shape, true);
     if (st != FEDRAG_OK) return st;
-    if (L_q < 0 || L_kv < 0) return FEDRAG_ERR_SHAPE;
+    if (L_q < 0 || L_kv < 0 || L_q > INT32_MAX || L_kv > INT32_MAX) return FEDRAG_ERR_SHAPE;
     if (!Qs || !O_part || !lse) return FEDRAG_ERR_NULL;
     if (L_kv > 0 && (!Ks || !Vs)) return FEDRAG_ERR_NULL;
     int64_t nq, nk;
