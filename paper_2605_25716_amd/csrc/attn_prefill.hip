@@ -2,7 +2,6 @@
 // per head against one KV shard, non-causal.  MFMA-bound, with the softmax VALU work a close second, so the kernel
 // is organised to let the two overlap:
 //   * one workgroup = 8 waves (two per SIMD) x 32 query rows = 256 query rows of one (sequence, query head);
-//     while one wave of a SIMD is in its MFMA phase the other runs its softmax;
 //   * K'/V' tiles of 64 keys are shared by the 8 waves through a double-buffered LDS stage (one barrier per
 //     tile); the next tile's global loads fly during the current tile's arithmetic;
 //   * both products are computed transposed, S^T = K' Q'^T and O^T = V'^T P^T (32x32x16 MFMA), so the fp32
@@ -22,9 +21,6 @@ constexpr int kPreQTile = kPreWaves * kPreQ;  // query rows per workgroup
 constexpr int kPreK = 64;                     // keys per LDS tile
 constexpr int kPreKPad = 16;                  // bytes of row padding, K' tile: 16-byte operand reads, 32 rows
 constexpr int kPreVPad = 64;                  // bytes of row padding, V' tile: transposing reads, 4 rows x 64 bytes
-#ifndef FEDRAG_PRE_PRIO
-#define FEDRAG_PRE_PRIO 1  // 0: equal wave priorities; 1: first four waves high; 2: raised during MFMA phases
-#endif
 
 typedef short s16x4_t __attribute__((ext_vector_type(4)));
 
@@ -128,12 +124,6 @@ __global__ __launch_bounds__(kPreThreads, 1) void prefill_attn_kernel(const type
     const int gq = lane / 16;
     const int v_rd = (4 * lh + s16 / 4) * VROW + ((gq % 2) * 16 + 4 * (s16 % 4)) * 2;
 
-#if FEDRAG_PRE_PRIO == 1
-    // The two waves that share a SIMD run identical instruction streams and leave every barrier together; giving
-    // one of them priority makes it win each contested pipe, so the pair falls into complementary phases
-    // (one in its MFMA phase while the other is in its softmax) instead of contending in lockstep.
-    if (wave < kPreWaves / 2) __builtin_amdgcn_s_setprio(2);
-#endif
     if (L > 0) {
         load_tile(0);
         store_tile(0);
@@ -159,9 +149,6 @@ __global__ __launch_bounds__(kPreThreads, 1) void prefill_attn_kernel(const type
                 for (int ks = 0; ks < KS; ++ks)
                     kop[mt][ks] = *(const vec8*)(kt + mt * 32 * KROW + k_rd + ks * 32);
             __builtin_amdgcn_sched_barrier(0);  // keep the reads ahead of the MFMAs
-#if FEDRAG_PRE_PRIO == 2
-            __builtin_amdgcn_s_setprio(2);
-#endif
             s[0] = zero_vec<f32x16_t>();
             s[1] = zero_vec<f32x16_t>();
 #pragma unroll
@@ -169,9 +156,6 @@ __global__ __launch_bounds__(kPreThreads, 1) void prefill_attn_kernel(const type
                 s[0] = T::mfma32(kop[0][ks], qop[ks], s[0]);
                 s[1] = T::mfma32(kop[1][ks], qop[ks], s[1]);
             }
-#if FEDRAG_PRE_PRIO == 2
-            __builtin_amdgcn_s_setprio(0);
-#endif
         }
         // V'^T operands of the first two 16-key steps: requested now, consumed after the softmax
         auto read_vop = [&](int kk, int i) -> vec8 {
@@ -231,9 +215,6 @@ __global__ __launch_bounds__(kPreThreads, 1) void prefill_attn_kernel(const type
             for (int i = 0; i < MT; ++i) acc_o[i] *= alpha;
         }
         // O^T += V'^T P^T, 16 keys per step: contraction element e <-> key 16 kk + 8 (e / 4) + 4 lh + e % 4
-#if FEDRAG_PRE_PRIO == 2
-        __builtin_amdgcn_s_setprio(2);
-#endif
 #pragma unroll
         for (int kk = 0; kk < 2; ++kk)
 #pragma unroll
@@ -242,9 +223,6 @@ __global__ __launch_bounds__(kPreThreads, 1) void prefill_attn_kernel(const type
         for (int kk = 0; kk < 2; ++kk)
 #pragma unroll
             for (int i = 0; i < MT; ++i) acc_o[i] = T::mfma32(vop_b[kk][i], pop[2 + kk], acc_o[i]);
-#if FEDRAG_PRE_PRIO == 2
-        __builtin_amdgcn_s_setprio(0);
-#endif
         if (t + 1 < n_tiles) store_tile(buf ^ 1);
         __syncthreads();
     }

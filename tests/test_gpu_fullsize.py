@@ -1,0 +1,141 @@
+"""GPU parity at the full sizes of the measured configurations, in the launch configuration bench.py times.
+
+Inputs are drawn on the GPU by the seeded generator (one KV shard of the configuration).  The oracle cannot
+recompute whole tensors of this size, so a seeded sample of (sequence, KV head) units is checked one by one:
+  * scramble_kv: the unit's plaintext rows are copied to the host, scrambled by the oracle and compared with
+    the GPU's rows;
+  * partial_attn: the sampled units of the device K'/V' (and all of Q') are then REPLACED by the oracle's
+    rounded result, so that both sides consume identical bits that never came from the HIP path, and the unit's
+    partial output and log-sum-exp are compared with the oracle's;
+  * everything the sample does not cover is held to properties that are true at any size (finite outputs,
+    log-sum-exp bounded by max logit bound, outputs inside the convex hull bound of V').
+"""
+import numpy as np
+import pytest
+import torch
+
+import parity as PT
+from paper_2605_25716_amd import binding as fb
+from paper_2605_25716_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+
+
+def rounded(a64, dtype):
+    return torch.from_numpy(np.ascontiguousarray(a64)).to(dtype)
+
+
+def shard_on_gpu(cfg, shard=0):
+    dt = W.torch_dtype(cfg.dtype)
+    Q = W.activations(cfg.batch, cfg.n_q_heads, cfg.L_q, cfg.d_head, seed=cfg.seed, tensor_id=W.TID_Q,
+                      outliers=cfg.outliers, dtype=dt, device=DEV)
+    K = W.activations(cfg.batch, cfg.n_kv_heads, cfg.L_kv, cfg.d_head, seed=cfg.seed, tensor_id=W.TID_K + shard,
+                      outliers=cfg.outliers, outlier_id=W.TID_K, dtype=dt, device=DEV)
+    V = W.activations(cfg.batch, cfg.n_kv_heads, cfg.L_kv, cfg.d_head, seed=cfg.seed, tensor_id=W.TID_V + shard,
+                      outliers=cfg.outliers, outlier_id=W.TID_V, dtype=dt, device=DEV)
+    keys = W.make_keys(cfg.n_kv_heads, cfg.d_head, cfg.L_q, cfg.L_kv, cfg.n_shards, seed=cfg.seed, dtype=dt)
+    return Q, K, V, keys
+
+
+def run_fullsize(oracle, cfg, n_units, q_rows_per_head=None, heads_per_unit=None):
+    dt = W.torch_dtype(cfg.dtype)
+    G = cfg.group
+    Q, K, V, keys = shard_on_gpu(cfg)
+    perm = keys.perm_kv[0]
+    phi = {k: getattr(keys, k).to(DEV) for k in ("phi_q", "phi_k", "phi_v")}
+    perm_q_dev = None if keys.perm_q is None else keys.perm_q.to(DEV)
+
+    # ---- Enc on the GPU, whole tensors
+    Ks, Vs = fb.fedrag_scramble_kv(K, V, phi["phi_k"], phi["phi_v"], perm.to(DEV), n_q_heads=cfg.n_q_heads)
+    Qs = fb.fedrag_scramble_q(Q, phi["phi_q"], perm_q_dev)
+    torch.cuda.synchronize()
+
+    rng = np.random.default_rng(cfg.seed + 17)
+    all_units = [(b, g) for b in range(cfg.batch) for g in range(cfg.n_kv_heads)]
+    units = [all_units[i] for i in rng.choice(len(all_units), size=min(n_units, len(all_units)), replace=False)]
+    oracle_units = {}
+    for (b, g) in units:
+        Kp, Vp = K[b:b + 1, g:g + 1].cpu(), V[b:b + 1, g:g + 1].cpu()
+        Ko = oracle.scramble(Kp, keys.phi_k[g:g + 1], perm)
+        Vo = oracle.scramble(Vp, keys.phi_v[g:g + 1], perm)
+        PT.check_scramble(Ks[b:b + 1, g:g + 1], Ko, Kp, keys.phi_k[g:g + 1], perm, 1, dt, f"K' unit {(b, g)}")
+        PT.check_scramble(Vs[b:b + 1, g:g + 1], Vo, Vp, keys.phi_v[g:g + 1], perm, 1, dt, f"V' unit {(b, g)}")
+        Ko, Vo = rounded(Ko, dt), rounded(Vo, dt)
+        Ks[b:b + 1, g:g + 1] = Ko.to(DEV)   # from here on both sides read the oracle's bits
+        Vs[b:b + 1, g:g + 1] = Vo.to(DEV)
+        # Q' of the unit's query heads
+        hs = list(range(g * G, (g + 1) * G))
+        if heads_per_unit is not None:
+            hs = [hs[i] for i in rng.choice(G, size=heads_per_unit, replace=False)]
+        Qp = Q[b:b + 1, hs].cpu()
+        Qo = np.concatenate([oracle.scramble(Qp[:, i:i + 1], keys.phi_q[g:g + 1], keys.perm_q) for i in range(len(hs))], 1)
+        PT.check_scramble(Qs[b:b + 1, hs], Qo, Qp, keys.phi_q[g:g + 1].repeat(len(hs), 1, 1), keys.perm_q, 1, dt,
+                          f"Q' unit {(b, g)}")
+        Qo = rounded(Qo, dt)
+        Qs[b:b + 1, hs] = Qo.to(DEV)
+        oracle_units[(b, g)] = (hs, Qo, Ko, Vo)
+
+    # ---- the Compute Node's call, whole shard
+    O, lse = fb.fedrag_partial_attn(Qs, Ks, Vs)
+    torch.cuda.synchronize()
+    worst_o = worst_l = 0.0
+    for (b, g), (hs, Qo, Ko, Vo) in oracle_units.items():
+        for i, h in enumerate(hs):
+            rows = np.arange(cfg.L_q)
+            if q_rows_per_head is not None and cfg.L_q > q_rows_per_head:
+                rows = np.sort(rng.choice(cfg.L_q, size=q_rows_per_head, replace=False))
+            Or, lr = oracle.partial_attn(Qo[:, i:i + 1, rows], Ko, Vo)
+            eo, el = PT.check_attn(O[b:b + 1, h:h + 1][:, :, rows], lse[b:b + 1, h:h + 1][:, :, rows], Or, lr, dt,
+                                   f"{cfg.name} unit {(b, g)} head {h}")
+            worst_o, worst_l = max(worst_o, eo), max(worst_l, el)
+    print(f"{cfg.name}: sampled units {units}: worst O err {worst_o:.3e}, worst lse err {worst_l:.3e}")
+
+    # ---- properties over the whole output
+    assert torch.isfinite(O).all() and torch.isfinite(lse).all()
+    vmax = Vs.float().abs().amax(dim=(2,))                       # [B,Hkv,d]: |O| <= max_t |V'_t| per channel
+    bound = vmax.repeat_interleave(G, dim=1)[:, :, None, :] * (1 + 1e-2) + 1e-3
+    assert (O.abs() <= bound).all()
+    # ln L + min logit <= lse <= ln L + max logit, with |logit| <= |q||k| scale
+    qn = Qs.float().norm(dim=-1)                                 # [B,Hq,Lq]
+    kn = Ks.float().norm(dim=-1).amax(dim=-1).repeat_interleave(G, dim=1)[:, :, None]  # [B,Hq,1]
+    lim = qn * kn * cfg.d_head ** -0.5
+    lnL = float(np.log(cfg.L_kv))
+    assert (lse <= lnL + lim + 1e-2).all() and (lse >= lnL - lim - 1e-2).all()
+    return O, lse
+
+
+def test_llama8b_decode_shard_full_size(oracle):
+    run_fullsize(oracle, W.CONFIGS["llama8b_decode"], n_units=6)
+
+
+def test_rag_prefill_full_size(oracle):
+    run_fullsize(oracle, W.CONFIGS["rag_prefill"], n_units=2, q_rows_per_head=96, heads_per_unit=2)
+
+
+def test_long_decode_shard_full_size(oracle):
+    run_fullsize(oracle, W.CONFIGS["long_decode"], n_units=2)
+
+
+def test_mixed70b_decode_shard_full_size(oracle):
+    run_fullsize(oracle, W.CONFIGS["mixed70b_decode"], n_units=4)
+
+
+def test_mixed70b_prefill_shard_full_size(oracle):
+    run_fullsize(oracle, W.CONFIGS["mixed70b_prefill"], n_units=1, q_rows_per_head=64, heads_per_unit=2)
+
+
+def test_merge_and_unscramble_at_decode_size(oracle):
+    cfg = W.CONFIGS["llama8b_decode"]
+    g = torch.Generator().manual_seed(cfg.seed)
+    S, B, H, Lq, d = cfg.n_shards, cfg.batch, cfg.n_q_heads, cfg.L_q, cfg.d_head
+    parts = torch.randn((S, B, H, Lq, d), generator=g) * 2
+    lses = torch.randn((S, B, H, Lq), generator=g) * 20
+    keys = W.make_keys(cfg.n_kv_heads, d, Lq, 8, 1, seed=cfg.seed, dtype=torch.bfloat16)
+    O, l = fb.fedrag_lse_merge(parts.to(DEV), lses.to(DEV), n_kv_heads=cfg.n_kv_heads)
+    Or, lr = oracle.lse_merge(parts, lses)
+    assert PT.rel_normwise(O, Or) <= PT.TOL_F32_REL and PT.rel_normwise(l, lr) <= PT.TOL_F32_REL
+    Om = torch.from_numpy(Or).float()
+    out = fb.fedrag_unscramble(Om.to(DEV), keys.phi_v_inv.to(DEV), None)
+    ref = oracle.unscramble(Om, keys.phi_v_inv, None)
+    assert PT.rel_normwise(out, ref) <= PT.TOL_F32_REL
