@@ -22,6 +22,13 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16 MFMA
 
+# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by a 1 GiB copy kernel of
+# known size; see profiles/bench_llama8b_decode_hbm_traffic.txt for the commands and the readings).
+MEASURED_TRAFFIC_BYTES = {
+    "scramble_kv": int((513.14 + 512.02) * 2**20),
+    "partial_attn": int((512.48 + 0.51) * 2**20),
+}
+
 
 def parse():
     ap = argparse.ArgumentParser()
@@ -30,7 +37,10 @@ def parse():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-prefill", action="store_true", help="skip the RAG-prefill leg")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
-    ap.add_argument("--cpu-seqs", type=int, default=4, help="sequences of shard 0 the oracle is timed on")
+    ap.add_argument("--cpu-shards", type=int, default=4, help="KV shards (all sequences) the oracle is timed on")
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="also run one 1 GiB device-to-device copy kernel before the timed region: a kernel of known "
+                         "traffic to scale rocprofv3 FETCH_SIZE / WRITE_SIZE readings with")
     return ap.parse_args()
 
 
@@ -144,33 +154,36 @@ def prefill_leg(torch, W, fb, dev, steps, warmup):
                          "kernel": "prefill_attn_kernel<BF16,128>"}}
 
 
-def cpu_leg(torch, W, g, n_seqs):
-    """The oracle, as it stands, on shard 0 of the first n_seqs sequences: scramble_q, scramble K and V,
-    partial attention, merge (one shard), unscramble.  Bytes are the same algorithmic bytes, scaled."""
+def cpu_leg(torch, W, g, n_shards):
+    """The oracle, as it stands, on the first n_shards KV shards (all sequences): scramble_q, then per shard scramble
+    of K and V and partial attention, then merge and unscramble - the same step the GPU is timed on."""
+    import numpy as np
     import oracle
     cfg = g["cfg"]
-    n_seqs = min(n_seqs, cfg.batch)
-    Q = g["Q"][:n_seqs].cpu()
-    K = g["K"][0][:n_seqs].cpu()
-    V = g["V"][0][:n_seqs].cpu()
+    n_shards = max(1, min(n_shards, cfg.n_shards))
     k = g["keys"]
-    perm = k.perm_kv[0]
+    Q = g["Q"].cpu()
+    Kc = [g["K"][s].cpu() for s in range(n_shards)]
+    Vc = [g["V"][s].cpu() for s in range(n_shards)]
     t0 = time.perf_counter()
     Qs = oracle.scramble(Q, k.phi_q, None)
-    Ks = oracle.scramble(K, k.phi_k, perm)
-    Vs = oracle.scramble(V, k.phi_v, perm)
-    o, l = oracle.partial_attn(Qs, Ks, Vs)
-    O, lse = oracle.lse_merge(o[None], l[None])
+    parts, lses = [], []
+    for s in range(n_shards):
+        Ks = oracle.scramble(Kc[s], k.phi_k, k.perm_kv[s])
+        Vs = oracle.scramble(Vc[s], k.phi_v, k.perm_kv[s])
+        o, l = oracle.partial_attn(Qs, Ks, Vs)
+        parts.append(o); lses.append(l)
+        del Ks, Vs
+    O, lse = oracle.lse_merge(np.stack(parts), np.stack(lses))
     out = oracle.unscramble(O, k.phi_v_inv, None)
     dt = time.perf_counter() - t0
-    frac = n_seqs / cfg.batch
     b = g["bytes"]
-    nbytes = frac * (b["scramble_q"] + b["scramble_kv"] + b["partial_attn"] + b["unscramble"]) + \
-        2 * frac * b["lse_merge"] / (cfg.n_shards + 1)
+    nbytes = b["scramble_q"] + n_shards * (b["scramble_kv"] + b["partial_attn"]) + \
+        b["lse_merge"] * (n_shards + 1) / (cfg.n_shards + 1) + b["unscramble"]
     return {"value": nbytes / dt / 1e9, "unit": "GB/s", "cores": oracle.get_threads(), "kind": "oracle",
-            "seconds": dt,
-            "sample": f"shard 0 of {cfg.n_shards}, sequences 0..{n_seqs - 1} of {cfg.batch}: all five calls in fp64 "
-                      f"({nbytes / 2**20:.0f} MiB of the step's algorithmic bytes)"}
+            "seconds": round(dt, 3),
+            "sample": f"KV shards 0..{n_shards - 1} of {cfg.n_shards}, all {cfg.batch} sequences: the whole step in fp64 "
+                      f"({nbytes / 2**30:.2f} GiB of the step's {g['step_bytes'] / 2**30:.2f} GiB algorithmic bytes)"}
 
 
 def main():
@@ -191,6 +204,13 @@ def main():
     torch.cuda.set_device(0)
 
     g = decode_workload(torch, W, fb, dev)
+    if args.pmc_calibration:
+        a = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+        b = torch.empty_like(a)
+        a.fill_(1)
+        b.copy_(a)          # the reference kernel: reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del a, b
     for _ in range(args.warmup):
         decode_step(fb, g)
     torch.cuda.synchronize()
@@ -212,7 +232,7 @@ def main():
     kernel_of = {"scramble_kv": "scramble_rows_kernel<BF16,128>", "partial_attn": "decode_attn_kernel<BF16,128>"}
     dom = max(kernel_of, key=lambda n: calls[n]["total_ms"])
     roofline = {"bound": "hbm", "achieved": per_call[dom]["GB/s"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(per_call[dom]["GB/s"] / HBM_PEAK_GBS, 4), "traffic": None,
+                "frac": round(per_call[dom]["GB/s"] / HBM_PEAK_GBS, 4), "traffic": MEASURED_TRAFFIC_BYTES.get(dom),
                 "kernel": kernel_of[dom], "call": dom, "avg_us": per_call[dom]["avg_us"],
                 "bytes_per_launch": g["bytes"][dom]}
     # the spec kernel on its own: K'/V' streaming of partial_attn (+ split merge) over the 4 shards
@@ -233,7 +253,7 @@ def main():
     if not args.no_prefill:
         line["prefill"] = prefill_leg(torch, W, fb, dev, max(5, args.steps // 2), args.warmup)
     if not args.no_cpu:
-        line["cpu_baseline"] = cpu_leg(torch, W, g, args.cpu_seqs)
+        line["cpu_baseline"] = cpu_leg(torch, W, g, args.cpu_shards)
     print(json.dumps(line))
 
 
