@@ -30,16 +30,21 @@ struct ScrambleJob {
     void* Y;
 };
 
-// blockIdx.x = (bh * chunks + chunk); blockIdx.y selects the job (K or V).
-// Wave w of the workgroup owns the 32-row tiles w, w+4, ... of the chunk.  A ring of NBUF register tile sets
-// keeps NBUF-1 gathered tiles (8 KiB each) in flight per wave behind the LDS staging and the MFMAs; the gather
-// indices of a tile are fetched one step before its rows.
+// blockIdx.x = (head * members + member) * b_groups + bg; blockIdx.y selects the job (K or V).
+// The `members` workgroups of one (job, head) share that head's Phi and sweep the sequences b = 0..B-1 together:
+// in every [L, d] slab member m takes the contiguous m-th part of the rows, as 32-row tiles dealt round-robin to
+// its 4 waves.  So at any moment the chip reads and writes a few slabs (one per job and head) rather than one
+// distant region per workgroup, and Phi is staged once per workgroup for all sequences.  (When the slabs are too
+// short to occupy the chip that way - decode queries - the sequences are dealt to b_groups workgroups instead.)
+// A ring of NBUF register tile sets keeps NBUF-1 gathered tiles (8 KiB each) in flight per wave behind the LDS
+// staging and the MFMAs (it runs straight through the slab boundaries); the gather indices of a tile are fetched
+// one step before its rows.  Tiles that start past the end of a slab are computed on clamped rows and not stored.
 template <class T, int D>
 __global__ __launch_bounds__(kScrThreads, 1) void scramble_rows_kernel(ScrambleJob job0, ScrambleJob job1,
                                                                        const int32_t* __restrict__ perm,
                                                                        int64_t perm_batch_stride,  // 0 or L
-                                                                       int H, int G, int64_t L, int chunks,
-                                                                       int tiles_per_wave) {
+                                                                       int B, int H, int G, int64_t L, int members,
+                                                                       int tiles_per_slab, int b_groups) {
     typedef typename T::elem elem;
     typedef typename T::vec8 vec8;
     typedef typename T::vec4 vec4;
@@ -62,10 +67,9 @@ __global__ __launch_bounds__(kScrThreads, 1) void scramble_rows_kernel(ScrambleJ
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);  // wave-uniform
     const int lane = tid % kWave;
-    const int bh = blockIdx.x / chunks;
-    const int chunk = blockIdx.x % chunks;
-    const int b = bh / H;
-    const int h = bh % H;
+    const int h = blockIdx.x / (members * b_groups);
+    const int member = (blockIdx.x / b_groups) % members;
+    const int bg = blockIdx.x % b_groups;  // this workgroup takes sequences bg, bg + b_groups, ...
 
     // ---- stage Phi^T[n][k] = Phi[k][n] in LDS (once per workgroup) ----
     {
@@ -91,49 +95,48 @@ __global__ __launch_bounds__(kScrThreads, 1) void scramble_rows_kernel(ScrambleJ
             phi[mt][ks] = *(const vec8*)(&lds[(mt * 16 + lr) * LDP + ks * 32 + lq * 8]);
     __syncthreads();  // Phi^T is dead from here on; the buffer becomes the row tiles
 
-    const elem* X = (const elem*)job.X + (int64_t)bh * L * D;
-    elem* Y = (elem*)job.Y + (int64_t)bh * L * D;
-    const int32_t* pm = perm ? perm + (int64_t)b * perm_batch_stride : nullptr;
     elem* my = lds + wave * (kScrRows * LDP);
 
     const int ld_row = lane / CH;        // row within one wave-wide load
     const int ld_col = (lane % CH) * 8;  // element offset of this lane's 16 bytes
 
-    const int64_t chunk_row0 = (int64_t)chunk * tiles_per_wave * kScrWaves * kScrRows;
-    auto tile_row0 = [&](int i) { return chunk_row0 + (int64_t)(i * kScrWaves + wave) * kScrRows; };
-    // tiles of this wave that start inside [0, L)
-    int n_mine = 0;
-    {
-        const int64_t first = tile_row0(0);
-        if (first < L) {
-            const int64_t left = (L - first + kScrWaves * kScrRows - 1) / (kScrWaves * kScrRows);
-            n_mine = left < tiles_per_wave ? (int)left : tiles_per_wave;
-        }
-    }
+    // tile i of this wave: sequence b = i / tiles_per_slab, k-th tile of the wave inside this member's part
+    const int n_mine = ((B - bg + b_groups - 1) / b_groups) * tiles_per_slab;
+    auto tile_b = [&](int i) { return bg + (i / tiles_per_slab) * b_groups; };
+    auto tile_row0 = [&](int i) {
+        const int k = i % tiles_per_slab;
+        return ((int64_t)(member * tiles_per_slab + k) * kScrWaves + wave) * kScrRows;
+    };
+    auto slab_off = [&](int i) { return ((int64_t)tile_b(i) * H + h) * L * D; };
+    const elem* Xj = (const elem*)job.X;
+    elem* Yj = (elem*)job.Y;
 
     // gather indices of a tile: lane l (< 32) holds the source row of tile row l; rows past the end re-read
     // row L-1 (computed, never stored)
     auto load_idx = [&](int i) -> int32_t {
+        if (i >= n_mine) i = n_mine - 1;  // the index prefetch runs one tile past the end
         int64_t j = tile_row0(i) + (lane % kScrRows);
         if (j >= L) j = L - 1;
-        return pm ? pm[j] : (int32_t)j;
+        return perm ? perm[(int64_t)tile_b(i) * perm_batch_stride + j] : (int32_t)j;
     };
-    auto load_rows = [&](int32_t idx, vec8 (&buf)[NI]) {
+    auto load_rows = [&](int i, int32_t idx, vec8 (&buf)[NI]) {
+        const elem* X = Xj + slab_off(i);
 #pragma unroll
-        for (int i = 0; i < NI; ++i) {
-            const int64_t src = __shfl(idx, i * RPI + ld_row);
-            buf[i] = __builtin_nontemporal_load((const vec8*)(X + src * D + ld_col));
+        for (int k = 0; k < NI; ++k) {
+            const int64_t src = __shfl(idx, k * RPI + ld_row);
+            buf[k] = __builtin_nontemporal_load((const vec8*)(X + src * D + ld_col));
         }
     };
 
     auto step = [&](vec8 (&buf)[NI], int i, bool reload, int32_t& idx_next) {
         const int64_t row0 = tile_row0(i);
+        elem* Y = Yj + slab_off(i);
         // rows -> LDS tile
 #pragma unroll
         for (int k = 0; k < NI; ++k) *(vec8*)(&my[(k * RPI + ld_row) * LDP + ld_col]) = buf[k];
         wave_lds_fence();
         if (reload) {  // refill this register set with the tile NBUF steps ahead, then fetch the indices after it
-            load_rows(idx_next, buf);
+            load_rows(i + NBUF, idx_next, buf);
             idx_next = load_idx(i + NBUF + 1);
         }
 #pragma unroll
@@ -176,7 +179,7 @@ __global__ __launch_bounds__(kScrThreads, 1) void scramble_rows_kernel(ScrambleJ
     int32_t idx_next = 0;
 #pragma unroll
     for (int j = 0; j < NBUF; ++j)
-        if (j < n_mine) load_rows(load_idx(j), buf[j]);
+        if (j < n_mine) load_rows(j, load_idx(j), buf[j]);
     if (NBUF < n_mine) idx_next = load_idx(NBUF);
     int i = 0;
     // steady state: tiles i+NBUF .. exist for every set, index prefetch may run one tile past the end (clamped)
@@ -268,17 +271,21 @@ static int ceil_div_i64(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
 template <class T, int D>
 static hipError_t launch_scramble16(const RowsJob& j, hipStream_t stream) {
     const int64_t rows_per_pass = kScrWaves * kScrRows;  // rows one workgroup covers per ring step
-    const int64_t passes = (j.L + rows_per_pass - 1) / rows_per_pass;
-    // about one workgroup per CU over the whole launch: long streams per wave, Phi staged once per workgroup
-    const int64_t total = passes * j.BH * j.n_jobs;
-    int tpw = (int)((total + FEDRAG_SCR_WGS - 1) / FEDRAG_SCR_WGS);
-    if (tpw < 1) tpw = 1;
-    if (tpw > 4096) tpw = 4096;
-    const int chunks = ceil_div_i64(passes, tpw);
-    dim3 grid((unsigned)(j.BH * chunks), (unsigned)j.n_jobs);
+    const int64_t passes = (j.L + rows_per_pass - 1) / rows_per_pass;  // per [L, d] slab
+    // about one workgroup per CU over the whole launch, split evenly over (job, head); never more members than a
+    // slab has passes
+    int members = FEDRAG_SCR_WGS / (j.H * j.n_jobs);
+    if (members < 1) members = 1;
+    if ((int64_t)members > passes) members = (int)passes;
+    const int tiles_per_slab = ceil_div_i64(passes, members);
+    const int B = (int)(j.BH / j.H);
+    int b_groups = FEDRAG_SCR_WGS / (j.H * j.n_jobs * members);  // leftover parallelism goes to the sequences
+    if (b_groups < 1) b_groups = 1;
+    if (b_groups > B) b_groups = B;
+    dim3 grid((unsigned)(j.H * members * b_groups), (unsigned)j.n_jobs);
     ScrambleJob a{j.X[0], j.Phi[0], j.Y[0]}, b{j.X[1], j.Phi[1], j.Y[1]};
     hipLaunchKernelGGL((scramble_rows_kernel<T, D>), grid, dim3(kScrThreads), 0, stream, a, b, j.perm,
-                       j.perm_batch_stride, j.H, j.G, j.L, chunks, tpw);
+                       j.perm_batch_stride, B, j.H, j.G, j.L, members, tiles_per_slab, b_groups);
     return hipGetLastError();
 }
 
