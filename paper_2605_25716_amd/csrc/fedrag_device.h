@@ -69,6 +69,17 @@ __device__ __forceinline__ void wave_lds_fence() {
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 __device__ __forceinline__ float fast_log2(float x) { return __builtin_amdgcn_logf(x); }
 
+// Max / sum over the lane pair (l, l ^ 32).
+__device__ __forceinline__ float xor32_max(float x) { return fmaxf(x, __shfl_xor(x, 32)); }
+__device__ __forceinline__ float xor32_sum(float x) { return x + __shfl_xor(x, 32); }
+
+// Keep a value's computation above this point: the compiler may otherwise sink pure register arithmetic towards
+// its first use (past a barrier, into the next loop iteration), out of the scheduling region it was written for.
+template <class V>
+__device__ __forceinline__ void pin_here(V& v) {
+    asm volatile("" : "+v"(v));
+}
+
 // exp2(a - b) with the convention that a == -inf gives 0 even when b == -inf.
 __device__ __forceinline__ float exp2_diff(float a, float b) {
     return (a == -INFINITY) ? 0.0f : fast_exp2(a - b);
