@@ -25,6 +25,10 @@ constexpr int kPreThreads = kPreWaves * kWave;
 constexpr int kPreQ = 32;                     // query rows per wave (one 32-wide MFMA column tile)
 constexpr int kPreQTile = kPreWaves * kPreQ;  // query rows per workgroup
 constexpr int kPreK = 64;                     // keys per LDS tile
+#ifndef FEDRAG_PRE_PD
+#define FEDRAG_PRE_PD 4
+#endif
+constexpr int kPrePD = FEDRAG_PRE_PD;         // MFMA operands are read from LDS this many MFMAs ahead
 
 typedef short s16x4_t __attribute__((ext_vector_type(4)));
 
@@ -34,11 +38,6 @@ typedef short s16x4_t __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ u32x2_t lds_read_tr16(const char* p) {
     const s16x4_t v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4_t __attribute__((address_space(3)))*)p);
     return __builtin_bit_cast(u32x2_t, v);
-}
-
-template <int D>
-constexpr int prefill_lds_bytes() {
-    return 4 * kPreK * D * 2;  // two K' slots + two V' slots
 }
 
 template <class T, int D>
@@ -57,9 +56,9 @@ __global__ __launch_bounds__(kPreThreads, 1) void prefill_attn_kernel(const type
     constexpr int CH = D / 8;               // 16-byte chunks per row
     constexpr int LPT = (kPreK * CH) / kPreThreads;  // LDS-direct loads per thread per tile
 
-    extern __shared__ __attribute__((aligned(16))) char smem[];
-    char* const ks_ = smem;             // [2][64][ROWB]
-    char* const vs_ = smem + 2 * SLOT;  // [2][64][ROWB]
+    // One array per tile slot: distinct objects let the compiler see that the LDS-direct load filling one slot
+    // does not alias the LDS reads of another, so it does not make those reads wait for the load.
+    __shared__ __attribute__((aligned(16))) char ks0[SLOT], ks1[SLOT], vs0[SLOT], vs1[SLOT];
 
     // XCD-aware placement: consecutive workgroup ids are dealt round-robin to the 8 XCDs (one L2 each);
     // give every XCD whole (sequence, KV head) units so that the workgroups sharing K'/V' share an L2.
@@ -99,22 +98,26 @@ __global__ __launch_bounds__(kPreThreads, 1) void prefill_attn_kernel(const type
     for (int i = 0; i < MT; ++i) acc_o[i] = zero_vec<f32x16_t>();
     float m_run = -INFINITY, l_run = 0.f;
 
-    // ---- global -> LDS (direct).  One wave-wide load fills 64 consecutive 16-byte slots = 64 / CH tile rows.
-    // LDS slot p of row r holds global chunk p ^ swz(r): K' swz(r) = r % CH, V' swz(r) = (4 (r % 4)) % CH.
+    // ---- global -> LDS (direct buffer loads).  One wave-wide load fills 64 consecutive 16-byte slots = 64 / CH
+    // tile rows.  LDS slot p of row r holds global chunk p ^ swz(r): K' swz(r) = r % CH, V' swz(r) = (4 (r % 4)) % CH;
+    // both depend on r only through r % 16, which is the same for every load of a thread.  The buffer resource
+    // starts at the tile and covers the rest of the shard, so rows past the end of the shard arrive as zeros.
     constexpr int RPW = kWave / CH;  // rows per wave-wide load
-    const int ld_r = lane / CH;      // row within the load
-    const int ld_p = lane % CH;      // slot within the row
+    const int ld_r = wave * RPW + lane / CH;  // row within a group of kPreWaves * RPW rows
+    const int ld_p = lane % CH;               // slot within the row
+    const int ld_voff_k = ld_r * ROWB + ((ld_p ^ (ld_r % CH)) << 4);
+    const int ld_voff_v = ld_r * ROWB + ((ld_p ^ ((4 * (ld_r % 4)) % CH)) << 4);
+    static_assert((kPreWaves * RPW) % 16 == 0, "swizzle must not depend on the load index");
     auto load_tile = [&](const char* G_, char* slot_base, int tile, bool is_k) {
+        const int64_t byte0 = (int64_t)tile * SLOT;
+        const int64_t left = L * ROWB - byte0;
+        const int n_rec = (int)(left < 0x7fffffff ? left : 0x7fffffff);
+        const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)(G_ + byte0), 0, n_rec, 0x00020000);
 #pragma unroll
         for (int j = 0; j < LPT; ++j) {
-            const int r = (j * kPreWaves + wave) * RPW + ld_r;  // tile row
-            const int swz = is_k ? (r % CH) : ((4 * (r % 4)) % CH);
-            int key = tile * kPreK + r;  // L fits in 31 bits (checked by the caller)
-            if (key >= (int)L) key = (int)L - 1;  // rows past the end re-read the last row; masked in the softmax
-            const char* gp = G_ + (int64_t)key * ROWB + ((ld_p ^ swz) << 4);
             char* lp = slot_base + (j * kPreWaves + wave) * (RPW * ROWB);  // wave-uniform LDS base
-            __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)gp,
-                                             (void __attribute__((address_space(3)))*)lp, 16, 0, 0);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (void __attribute__((address_space(3)))*)lp, 16,
+                                                     is_k ? ld_voff_k : ld_voff_v, j * (kPreWaves * RPW * ROWB), 0, 0);
         }
     };
 
@@ -137,9 +140,10 @@ __global__ __launch_bounds__(kPreThreads, 1) void prefill_attn_kernel(const type
     }
 
     const int n_tiles = (int)((L + kPreK - 1) / kPreK);
-    f32x16_t S[2];   // S^T of the tile whose softmax runs in this iteration (two 32-key halves)
-    vec8 P[2][4];    // P[t & 1]: P^T operands of tile t, one per 16-key step
-    float alph[2];   // alph[t & 1]: rescale factor of the running output that goes with P(t)
+    f32x16_t S0;      // S^T of the current tile, keys 0..31
+    f32x16_t S1[2];   // S1[t & 1]: S^T of tile t, keys 32..63 (kept one iteration longer, see below)
+    vec8 P[2][4];     // P[t & 1]: P^T operands of tile t, one per 16-key step
+    float alph[2];    // alph[t & 1]: rescale factor of the running output that goes with P(t)
 
     auto read_vop = [&](const char* vt, int kk, int i) -> vec8 {
         const char* p = vt + kk * 16 * ROWB + v_off[i];
@@ -150,41 +154,76 @@ __global__ __launch_bounds__(kPreThreads, 1) void prefill_attn_kernel(const type
         return __builtin_bit_cast(vec8, w);
     };
 
-    // One pipeline iteration: A(t) = S^T(t) = K'(t) Q'^T, then C(t-1) = O^T += V'(t-1)^T P(t-1)^T issued together
-    // with B(t) = online softmax of tile t.  `par` carries t % 2 as a compile-time constant so that the
-    // double-buffered register sets are addressed statically.
+    // One pipeline iteration t, in two MFMA phases with vector work in their shadow:
+    //   A(t)   = S^T(t) = K'(t) Q'^T                     together with  B2(t-1) = probabilities of keys 32..63 of
+    //                                                                   tile t-1 (its maximum is already known);
+    //   C(t-1) = O^T += V'(t-1)^T P(t-1)^T               together with  B1(t) = row maximum of tile t, new running
+    //                                                                   maximum, rescale factor, probabilities of
+    //                                                                   keys 0..31 of tile t.
+    // Splitting the softmax of a tile over two phases gives both MFMA phases about the same vector load.
+    // `par` carries t % 2 as a compile-time constant so that the double-buffered register sets are addressed
+    // statically.  m_run is the running maximum after tile t-1 until B1(t) replaces it.
     auto iteration = [&](int t, auto par, bool doC, bool doAB, bool ldK, bool may_mask) {
         constexpr int p = decltype(par)::value;  // t & 1
         constexpr int q = 1 - p;                 // (t - 1) & 1 == (t + 1) & 1
-        if (ldK) load_tile(Kg, ks_ + q * SLOT, t + 1, true);    // K'(t+1) -> slot (t+1) & 1 (last read by A(t-1))
-        if (doAB) load_tile(Vg, vs_ + p * SLOT, t, false);      // V'(t)   -> slot t & 1     (last read by C(t-2))
+        constexpr int NM = 4 * MT;
+        static_assert(NM == 16 || NM == 8, "slice plans assume d = 128 or 64");
+        if (ldK) load_tile(Kg, q ? ks1 : ks0, t + 1, true);    // K'(t+1) -> slot (t+1) & 1 (last read by A(t-1))
+        if (doAB) load_tile(Vg, p ? vs1 : vs0, t, false);      // V'(t)   -> slot t & 1     (last read by C(t-2))
+        const bool steady = doC && doAB && !may_mask;
 
-        if (doAB) {  // A(t): lane gets query li and, per 32-key half mt, keys 8 (r / 4) + 4 lh + r % 4, r = 0..15
-            const char* kt = ks_ + p * SLOT;
-            vec8 kop[2][KS];
+        // --- A(t) and B2(t-1).  Lane gets query li and, per 32-key half, keys 8 (r / 4) + 4 lh + r % 4, r = 0..15.
+        // Contraction element e of step kk of the second product <-> key 16 kk + 8 (e / 4) + 4 lh + e % 4, so
+        // register r of half 1 goes to step 2 + r / 8, element r % 8.
+        const char* kt = p ? ks1 : ks0;
+        if (steady) {
+            constexpr int NA = 2 * KS;  // MFMAs of A: slice j -> half j % 2, contraction step j / 2
+            vec8 kop[NA];
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-                kop[0][ks] = *(const vec8*)(kt + k_off[ks]);
-                kop[1][ks] = *(const vec8*)(kt + 32 * ROWB + k_off[ks]);
-            }
-            S[0] = zero_vec<f32x16_t>();
-            S[1] = zero_vec<f32x16_t>();
+            for (int j = 0; j < kPrePD; ++j) kop[j] = *(const vec8*)(kt + (j % 2) * 32 * ROWB + k_off[j / 2]);
+            S0 = zero_vec<f32x16_t>();
+            S1[p] = zero_vec<f32x16_t>();
+            float psum = 0.f;
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-                S[0] = T::mfma32(kop[0][ks], qop[ks], S[0]);
-                S[1] = T::mfma32(kop[1][ks], qop[ks], S[1]);
-            }
-            // issue order: operands run four reads ahead of the MFMAs that consume them
-            __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+            for (int j = 0; j < NA; ++j) {
+                if (j + kPrePD < NA) kop[j + kPrePD] = *(const vec8*)(kt + ((j + kPrePD) % 2) * 32 * ROWB + k_off[(j + kPrePD) / 2]);
+                if (j % 2 == 0) S0 = T::mfma32(kop[j], qop[j / 2], S0);
+                else S1[p] = T::mfma32(kop[j], qop[j / 2], S1[p]);
+                const int r0 = (j * 16) / NA, r1 = ((j + 1) * 16) / NA;  // registers of half 1 handled here
 #pragma unroll
-            for (int j = 0; j < 2 * KS - 4; ++j) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                for (int r = r0; r < r1; ++r) {
+                    const float pe = fast_exp2(__builtin_fmaf(S1[q][r], scale_log2, -m_run));
+                    psum += pe;
+                    P[q][2 + r / 8][r % 8] = T::from_float(pe);
+                }
+                pin_here(psum);  // the slice's vector work stays in the slice
+                __builtin_amdgcn_sched_barrier(0);
             }
-            __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+            l_run += psum;
+        } else {
+            if (doC) {  // B2(t-1)
+                float psum = 0.f;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const float pe = fast_exp2(__builtin_fmaf(S1[q][r], scale_log2, -m_run));
+                    psum += pe;
+                    P[q][2 + r / 8][r % 8] = T::from_float(pe);
+                }
+                l_run += psum;
+            }
+            if (doAB) {
+                S0 = zero_vec<f32x16_t>();
+                S1[p] = zero_vec<f32x16_t>();
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) {
+                    S0 = T::mfma32(*(const vec8*)(kt + k_off[ks]), qop[ks], S0);
+                    S1[p] = T::mfma32(*(const vec8*)(kt + 32 * ROWB + k_off[ks]), qop[ks], S1[p]);
+                }
+            }
         }
         __builtin_amdgcn_sched_barrier(0);
-        const char* vt = vs_ + q * SLOT;
+        const char* vt = q ? vs1 : vs0;
         if (doC) {
             if (__builtin_amdgcn_ballot_w64(alph[q] != 1.0f) != 0) {  // wave-uniform: skip when no maximum moved
 #pragma unroll
@@ -192,30 +231,29 @@ __global__ __launch_bounds__(kPreThreads, 1) void prefill_attn_kernel(const type
             }
         }
         __builtin_amdgcn_sched_barrier(0);
-        // --- C(t-1) and B(t).  Contraction element e of step kk <-> key 16 kk + 8 (e / 4) + 4 lh + e % 4.
-        if (doC && doAB && !may_mask) {
-            // Steady state: the 4 MT MFMAs of C(t-1) and the online softmax of tile t are issued as 16 slices,
-            // one MFMA each, with scheduling fences between slices: a slice holds the MFMA, its share of the
-            // softmax (which runs in the MFMA's shadow) and the transposing reads of the operand four MFMAs
-            // ahead.  Softmax shares: slices 0-1 the row maximum, slice 2 the new running maximum and the rescale
-            // factor, slices 2-15 the 16 pairs of probabilities (exp2, sum, narrowing).
-            constexpr int NM = 4 * MT;
-            static_assert(NM == 16 || NM == 8, "slice plan assumes d = 128 or 64");
-            constexpr int NP = 16;                 // probability pairs
-            constexpr int FIRST = 2;               // first slice that produces probabilities
+        // --- C(t-1) and B1(t)
+        if (steady) {
+            // 4 MT slices of one MFMA each, with scheduling fences between slices: a slice holds the MFMA, its
+            // share of B1 and the transposing reads of the operand four MFMAs ahead.  Shares: slices 0-1 the row
+            // maximum, slice 2 the new running maximum and the rescale factor, slices 2.. the 16 probabilities.
+            constexpr int FIRST = 2;  // first slice that produces probabilities
             vec8 vop[NM];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) vop[j] = read_vop(vt, j / MT, j % MT);
-            float mx = S[0][0];
+            for (int j = 0; j < kPrePD; ++j) vop[j] = read_vop(vt, j / MT, j % MT);
+            float mx = S0[0];
             float m_new = 0.f, psum = 0.f;
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int j = 0; j < NM; ++j) {
-                if (j + 4 < NM) vop[j + 4] = read_vop(vt, (j + 4) / MT, (j + 4) % MT);
+                if (j + kPrePD < NM) vop[j + kPrePD] = read_vop(vt, (j + kPrePD) / MT, (j + kPrePD) % MT);
                 acc_o[j % MT] = T::mfma32(vop[j], P[q][j / MT], acc_o[j % MT]);
-                if (j < 2) {
+                if (j == 0) {
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) mx = fmaxf(mx, S[j][r]);
+                    for (int r = 1; r < 16; ++r) mx = fmaxf(mx, S0[r]);
+                }
+                if (j == 1) {
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) mx = fmaxf(mx, S1[p][r]);
                 }
                 if (j == FIRST) {
                     mx = xor32_max(mx);
@@ -223,18 +261,13 @@ __global__ __launch_bounds__(kPreThreads, 1) void prefill_attn_kernel(const type
                     alph[p] = exp2_diff(m_run, m_new);
                 }
                 if (j >= FIRST) {
-                    // pairs handled by this slice: spread NP pairs over slices FIRST .. NM-1
                     constexpr int NS = NM - FIRST;
-                    const int pr0 = ((j - FIRST) * NP) / NS, pr1 = ((j - FIRST + 1) * NP) / NS;
+                    const int r0 = ((j - FIRST) * 16) / NS, r1 = ((j - FIRST + 1) * 16) / NS;
 #pragma unroll
-                    for (int pr = pr0; pr < pr1; ++pr) {
-#pragma unroll
-                        for (int u = 0; u < 2; ++u) {
-                            const int f = 2 * pr + u;  // flattened score index: half f / 16, register f % 16
-                            const float pe = fast_exp2(__builtin_fmaf(S[f / 16][f % 16], scale_log2, -m_new));
-                            psum += pe;
-                            P[p][f / 8][f % 8] = T::from_float(pe);
-                        }
+                    for (int r = r0; r < r1; ++r) {
+                        const float pe = fast_exp2(__builtin_fmaf(S0[r], scale_log2, -m_new));
+                        psum += pe;
+                        P[p][r / 8][r % 8] = T::from_float(pe);
                     }
                 }
                 __builtin_amdgcn_sched_barrier(0);
@@ -248,41 +281,36 @@ __global__ __launch_bounds__(kPreThreads, 1) void prefill_attn_kernel(const type
 #pragma unroll
                     for (int i = 0; i < MT; ++i) acc_o[i] = T::mfma32(read_vop(vt, kk, i), P[q][kk], acc_o[i]);
             }
-            if (doAB) {  // online softmax of tile t over this lane's 32 keys and its partner lane's 32 keys
+            if (doAB) {  // B1(t); keys past the end of the shard get a score of -inf (also seen by B2(t) later)
                 const int key0 = t * kPreK;
                 if (key0 + kPreK > (int)L) {  // ragged last tile
 #pragma unroll
-                    for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-                        for (int r = 0; r < 16; ++r) {
-                            const int key = key0 + mt * 32 + 8 * (r / 4) + 4 * lh + (r % 4);
-                            if (key >= (int)L) S[mt][r] = -INFINITY;
-                        }
+                    for (int r = 0; r < 16; ++r) {
+                        const int key = key0 + 8 * (r / 4) + 4 * lh + (r % 4);
+                        if (key >= (int)L) S0[r] = -INFINITY;
+                        if (key + 32 >= (int)L) S1[p][r] = -INFINITY;
+                    }
                 }
-                float mx = S[0][0];
+                float mx = S0[0];
 #pragma unroll
-                for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) mx = fmaxf(mx, S[mt][r]);
+                for (int r = 0; r < 16; ++r) mx = fmaxf(mx, fmaxf(S0[r], S1[p][r]));
                 mx = xor32_max(mx);
                 const float m_new = fmaxf(m_run, mx * scale_log2);
                 alph[p] = exp2_diff(m_run, m_new);
                 float psum = 0.f;
 #pragma unroll
-                for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) {  // step kk = 2 mt + r / 8 holds registers r = 8 (kk % 2) .. +8
-                        const float pe = fast_exp2(__builtin_fmaf(S[mt][r], scale_log2, -m_new));
-                        psum += pe;
-                        P[p][2 * mt + r / 8][r % 8] = T::from_float(pe);
-                    }
+                for (int r = 0; r < 16; ++r) {
+                    const float pe = fast_exp2(__builtin_fmaf(S0[r], scale_log2, -m_new));
+                    psum += pe;
+                    P[p][r / 8][r % 8] = T::from_float(pe);
+                }
                 l_run = l_run * alph[p] + psum;
                 m_run = m_new;
             }
         }
         // keep this iteration's results above the barrier that follows (they are consumed in the next iteration)
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
+        for (int kk = 0; kk < 2; ++kk) {
             u32x4_t w = __builtin_bit_cast(u32x4_t, P[p][kk]);
             pin_here(w);
             P[p][kk] = __builtin_bit_cast(vec8, w);
@@ -295,7 +323,7 @@ __global__ __launch_bounds__(kPreThreads, 1) void prefill_attn_kernel(const type
     std::integral_constant<int, 1> odd;
 
     // prologue: K'(0)
-    load_tile(Kg, ks_, 0, true);
+    load_tile(Kg, ks0, 0, true);
     alph[0] = alph[1] = 1.0f;
     __syncthreads();
 
@@ -335,19 +363,12 @@ __global__ __launch_bounds__(kPreThreads, 1) void prefill_attn_kernel(const type
 template <class T, int D>
 static hipError_t launch_prefill_t(const AttnProblem& p, hipStream_t stream) {
     typedef typename T::elem elem;
-    static bool configured = false;  // opt in to 64 KiB of dynamic LDS once per kernel instantiation
-    if (!configured) {
-        hipError_t e = hipFuncSetAttribute((const void*)prefill_attn_kernel<T, D>,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, prefill_lds_bytes<D>());
-        if (e != hipSuccess) return e;
-        configured = true;
-    }
     const float scale_log2 = p.scale * kLog2e;
     const int q_tiles = (int)((p.Lq + kPreQTile - 1) / kPreQTile);
     const int n_units = p.B * p.Hkv;
     const int per_unit = (p.Hq / p.Hkv) * q_tiles;
     const int64_t grid = (int64_t)8 * ((n_units + 7) / 8) * per_unit;
-    hipLaunchKernelGGL((prefill_attn_kernel<T, D>), dim3((unsigned)grid), dim3(kPreThreads), prefill_lds_bytes<D>(),
+    hipLaunchKernelGGL((prefill_attn_kernel<T, D>), dim3((unsigned)grid), dim3(kPreThreads), 0,
                        stream, (const elem*)p.Q, (const elem*)p.K, (const elem*)p.V, p.Hq, p.Hkv, p.Lq, p.Lkv, q_tiles,
                        n_units, scale_log2, p.O, p.lse);
     return hipGetLastError();
