@@ -25,7 +25,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16 MFMA
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by a 1 GiB copy kernel of
 # known size; see profiles/bench_llama8b_decode_hbm_traffic.txt for the commands and the readings).
 MEASURED_TRAFFIC_BYTES = {
-    "scramble_kv": int((513.14 + 512.02) * 2**20),
+    "scramble_kv": int((516.46 + 512.02) * 2**20),
     "partial_attn": int((512.48 + 0.51) * 2**20),
 }
 
