@@ -179,6 +179,34 @@ def unscramble(O, PhiInv, perm=None):
     return out
 
 
+def structured(X, key, perm=None, scatter=False):
+    """Section 4.2 structured transform Phi = S1 P1 H P2 S2 applied factor by factor (never formed as a matrix).
+
+    X [B,H,L,d]; key = (a, g1, g2, b), each [Hkv,d]: scale, channel gather, normalised Sylvester Hadamard, channel
+    gather, scale.  perm None, [L] or [n_perm,L] int32; rows are gathered (Enc) or, with scatter=True, scattered (Dec).
+    """
+    X = _f64(X)
+    a, g1, g2, b = key
+    a, b = _f64(a), _f64(b)
+    g1, g2 = np.ascontiguousarray(_i32(g1)), np.ascontiguousarray(_i32(g2))
+    B, H, L, d = X.shape
+    Hkv = a.shape[0]
+    assert a.shape == (Hkv, d) and b.shape == (Hkv, d) and g1.shape == (Hkv, d) and g2.shape == (Hkv, d)
+    assert H % Hkv == 0 and d & (d - 1) == 0, "Sylvester's Hadamard matrix needs d a power of two"
+    perm = _i32(perm)
+    n_perm = 1
+    if perm is not None:
+        if perm.ndim == 1:
+            perm = perm[None, :]
+        n_perm = perm.shape[0]
+        assert perm.shape[1] == L and n_perm in (1, B)
+        perm = np.ascontiguousarray(perm)
+    out = np.empty_like(X)
+    _load().oracle_structured(_p(X), _p(a), _p(g1), _p(g2), _p(b), _p(perm), _c_int(n_perm), _c_int(int(scatter)),
+                              _c_int(B), _c_int(H), _c_int(H // Hkv), _c_i64(L), _c_int(d), _p(out))
+    return out
+
+
 def invert_perm(perm):
     perm = _i32(perm)
     inv = np.empty_like(perm)

@@ -298,6 +298,61 @@ void oracle_unscramble(const double *O, const double *PhiInv, const int32_t *per
     }
 }
 
+/* ------------------------------------------------------------------------ */
+/* The structured scrambling matrix of Section 4.2 ("Our construction"),      */
+/* Phi = S1 P1 H P2 S2, applied to row vectors factor by factor in the order */
+/* the factors are written: scale, channel permutation, normalised Hadamard, */
+/* channel permutation, scale.  Key of one KV head, permutations as gathers: */
+/*   u[i] = x[i] * a[i]                       (x S1)                         */
+/*   v[j] = u[g1[j]]                          (. P1)                         */
+/*   w[m] = sum_i v[i] Hs[i][m] / sqrt(d)     (. H),  Hs[i][m] = +1 or -1    */
+/*          according to the parity of popcount(i AND m): Sylvester's        */
+/*          construction, d a power of two                                   */
+/*   y[j] = w[g2[j]] * b[j]                   (. P2 S2)                      */
+/* Rows are gathered (scatter = 0: out row j <- in row perm[j], Enc) or      */
+/* scattered (scatter = 1: out row perm[i] <- in row i, Dec).                */
+/* ------------------------------------------------------------------------ */
+static int parity_of(unsigned x)
+{
+    int p = 0;
+    while (x) { p ^= (int)(x & 1u); x >>= 1; }
+    return p;
+}
+
+void oracle_structured(const double *X, const double *a, const int32_t *g1, const int32_t *g2,
+                       const double *b, const int32_t *perm, int n_perm, int scatter,
+                       int B, int H, int G, int64_t L, int d, double *out)
+{
+    const double norm = 1.0 / sqrt((double)d);
+#pragma omp parallel for collapse(2) schedule(dynamic, 1) num_threads(NTHREADS())
+    for (int bb = 0; bb < B; ++bb) {
+        for (int h = 0; h < H; ++h) {
+            const double *Xh = X + ((int64_t)bb * H + h) * L * d;
+            double *Yh = out + ((int64_t)bb * H + h) * L * d;
+            const int64_t ko = (int64_t)(h / G) * d;
+            const int32_t *pi = perm ? perm + (n_perm > 1 ? (int64_t)bb * L : 0) : NULL;
+            double *v = (double *)malloc(sizeof(double) * (size_t)d * 2);
+            double *w = v + d;
+            for (int64_t r = 0; r < L; ++r) {
+                const int64_t src = (pi && !scatter) ? (int64_t)pi[r] : r;
+                const int64_t dst = (pi && scatter) ? (int64_t)pi[r] : r;
+                for (int j = 0; j < d; ++j) {
+                    const int i = g1[ko + j];
+                    v[j] = Xh[src * d + i] * a[ko + i];
+                }
+                for (int m = 0; m < d; ++m) {
+                    double acc = 0.0;
+                    for (int i = 0; i < d; ++i)
+                        acc += parity_of((unsigned)i & (unsigned)m) ? -v[i] : v[i];
+                    w[m] = acc * norm;
+                }
+                for (int j = 0; j < d; ++j) Yh[dst * d + j] = w[g2[ko + j]] * b[ko + j];
+            }
+            free(v);
+        }
+    }
+}
+
 /* inv[perm[j]] = j : the permutation that undoes the gather `perm`. */
 void oracle_invert_perm(const int32_t *perm, int64_t L, int32_t *inv)
 {

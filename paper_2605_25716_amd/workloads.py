@@ -184,6 +184,71 @@ def make_keys(n_kv_heads: int, d_head: int, L_q: int, L_kv: int, n_shards: int, 
                 perm_q, perm_kv, phi_kq, phi_v)
 
 
+@dataclass
+class StructuredKeys:
+    """Keys of the structured form Phi = S1 P1 H P2 S2 (Section 4.2), never multiplied out.
+
+    Each of q, k, v, v_inv is a tuple (scale_in [Hkv,d] fp32, perm_in [Hkv,d] int32, perm_out [Hkv,d] int32,
+    scale_out [Hkv,d] fp32) with the permutations as gathers: y = (((x * scale_in)[perm_in]) H)[perm_out] * scale_out.
+    k is the inverse transpose of q (same permutations, reciprocal scales) and v_inv the inverse of v (inverse
+    permutations swapped, reciprocal scales swapped).  scale_in of q, k, v holds values the storage dtype represents
+    exactly: the 16-bit kernels fold it into their +-1 operand matrix.
+    """
+    q: tuple
+    k: tuple
+    v: tuple
+    v_inv: tuple
+    perm_q: Optional[torch.Tensor]
+    perm_kv: List[torch.Tensor]
+
+
+def make_structured_keys(n_kv_heads: int, d_head: int, L_q: int, L_kv: int, n_shards: int, *, seed: int,
+                         dtype: torch.dtype, lo: float = 0.125, hi: float = 8.0, use_s2: bool = True,
+                         pow2: bool = False, n_perm: int = 1, batch: int = 1,
+                         permute_q: Optional[bool] = None) -> StructuredKeys:
+    """Draw S1, P1, P2, S2 per KV head for Phi_KQ and Phi_V: magnitudes log-uniform in [lo, hi] (powers of two with
+    pow2=True), random signs, uniform permutations; use_s2=False leaves S2 out (all ones)."""
+    rng = np.random.default_rng([seed ^ KEY_SEED_XOR, 0x5350])
+
+    def diag(on=True):
+        if not on:
+            return np.ones((n_kv_heads, d_head))
+        e = rng.uniform(np.log2(lo), np.log2(hi), size=(n_kv_heads, d_head))
+        mag = np.exp2(np.round(e)) if pow2 else np.exp2(e)
+        return mag * rng.choice([-1.0, 1.0], size=(n_kv_heads, d_head))
+
+    def perms():
+        return np.stack([rng.permutation(d_head) for _ in range(n_kv_heads)]).astype(np.int32)
+
+    def inv(g):
+        out = np.empty_like(g)
+        for h in range(g.shape[0]):
+            out[h, g[h]] = np.arange(g.shape[1], dtype=g.dtype)
+        return out
+
+    f32 = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32))
+    i32 = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32))
+    out = {}
+    for name in ("kq", "v"):
+        a = _round_to(diag(), dtype)          # stored exactly by the storage dtype
+        g1, g2 = perms(), perms()
+        b = diag(use_s2).astype(np.float32).astype(np.float64)
+        out[name] = (a, g1, g2, b)
+    a, g1, g2, b = out["kq"]
+    key_q = (f32(a), i32(g1), i32(g2), f32(b))
+    key_k = (f32(_round_to(1.0 / a, dtype)), i32(g1), i32(g2), f32(1.0 / b))
+    a, g1, g2, b = out["v"]
+    key_v = (f32(a), i32(g1), i32(g2), f32(b))
+    key_v_inv = (f32(1.0 / b), i32(inv(g2)), i32(inv(g1)), f32(1.0 / a))
+    if permute_q is None:
+        permute_q = L_q > 1
+    perm_q = torch.from_numpy(rng.permutation(L_q).astype(np.int32)) if permute_q else None
+    assert n_perm in (1, batch)
+    perm_kv = [torch.from_numpy(np.stack([rng.permutation(L_kv) for _ in range(n_perm)]).astype(np.int32))
+               for _ in range(n_shards)]
+    return StructuredKeys(key_q, key_k, key_v, key_v_inv, perm_q, perm_kv)
+
+
 # ----------------------------------------------------------------------------- whole cases
 TID_Q, TID_K, TID_V = 1, 100, 200  # random-stream ids; shard s uses TID_K + s, TID_V + s
 
