@@ -151,6 +151,28 @@ def graph_leg(torch, fb, g, steps):
     return 1e3 * (time.perf_counter() - t0) / steps
 
 
+def structured_leg(torch, W, fb, g, dev, steps, warmup):
+    """Enc of one KV shard with the keys in structured form (S1 P1 H P2 S2 by its factors): same bytes as scramble_kv."""
+    cfg = g["cfg"]
+    dt = W.torch_dtype(cfg.dtype)
+    ks = W.make_structured_keys(cfg.n_kv_heads, cfg.d_head, cfg.L_q, cfg.L_kv, 1, seed=cfg.seed, dtype=dt)
+    kk, kv = tuple(t.to(dev) for t in ks.k), tuple(t.to(dev) for t in ks.v)
+    perm = ks.perm_kv[0].to(dev)
+    call = lambda: fb.fedrag_scramble_kv_structured(g["K"][0], g["V"][0], kk, kv, perm, n_q_heads=cfg.n_q_heads,
+                                                    K_out=g["Ks"][0], V_out=g["Vs"][0])
+    for _ in range(warmup):
+        call()
+    torch.cuda.synchronize()
+    timer = CallTimer(torch)
+    for _ in range(steps):
+        timer.run("scramble_kv_structured", call)
+    torch.cuda.synchronize()
+    t = timer.summary()["scramble_kv_structured"]
+    gbs = g["bytes"]["scramble_kv"] / (t["avg_us"] * 1e-6) / 1e9
+    return {"call": "scramble_kv_structured", "avg_us": round(t["avg_us"], 2), "bytes": g["bytes"]["scramble_kv"],
+            "GB/s": round(gbs, 1), "frac_hbm": round(gbs / HBM_PEAK_GBS, 4)}
+
+
 def prefill_leg(torch, W, fb, dev, steps, warmup):
     """RAG prefill: partial_attn alone, 2048 queries x 16384 keys, 32/8 heads, d 128, bf16."""
     cfg = W.CONFIGS["rag_prefill"]
@@ -294,6 +316,7 @@ def main():
                                     "synchronisations (outputs checked equal to the eager ones bit for bit); "
                                     "'eager' = the same K steps launched call by call from Python")
     line["frac_hbm"] = round(line["value"] / HBM_PEAK_GBS, 4)
+    line["structured"] = structured_leg(torch, W, fb, g, dev, args.steps, args.warmup)
     if not args.no_prefill:
         line["prefill"] = prefill_leg(torch, W, fb, dev, max(5, args.steps // 2), args.warmup)
     if not args.no_cpu:

@@ -125,6 +125,45 @@ fedrag_status fedrag_unscramble(const fedrag_shape* shape, int64_t L_q, const fl
                                 const float* phi_v_inv, const int32_t* perm_q,
                                 float* O_out, void* stream);
 
+/*
+ * The structured scrambling matrix of Section 4.2 ("Our construction"),  Phi = S1 P1 H P2 S2, given by its factors
+ * instead of as a d x d matrix.  One key per transform; the struct itself is HOST memory holding four DEVICE
+ * pointers, each to a [n_kv_heads, d] array (4-byte aligned), with both channel permutations as gathers:
+ *     u[i] = x[i] * scale_in[i];  v[j] = u[perm_in[j]];  w = v . H;  y[j] = w[perm_out[j]] * scale_out[j]
+ * where H[i][m] = (-1)^popcount(i & m) / sqrt(d) is Sylvester's Hadamard matrix, normalised.
+ * From a key (a, g1, g2, b) of Phi the caller derives  Phi^{-T} = (1/a, g1, g2, 1/b)  and
+ * Phi^{-1} = (1/b, g2^{-1}, g1^{-1}, 1/a)  (P and H are orthogonal, H is symmetric).
+ * perm_in / perm_out must be permutations of 0..d-1 (not checked; indices are masked into range).
+ * For 16-bit storage the kernels multiply the rows by the matrix S1 P1 Hs P2 (Hs = the +-1 matrix) on the matrix
+ * cores, its entries +-scale_in[i] narrowed to the storage type - give scale_in values that type represents exactly -
+ * and apply scale_out / sqrt(d) to the fp32 sums: every product in a sum is exact and nothing is rounded before the
+ * one final narrowing.  For fp32 data everything is fp32.
+ */
+typedef struct {
+    const float*   scale_in;   /* S1 diagonal            [Hkv, d] */
+    const int32_t* perm_in;    /* P1 as a gather         [Hkv, d] */
+    const int32_t* perm_out;   /* P2 as a gather         [Hkv, d] */
+    const float*   scale_out;  /* S2 diagonal (ones = the variant without S2 of Section 7.5)  [Hkv, d] */
+} fedrag_structured_key;
+
+/* fedrag_scramble_kv with Phi_KQ^{-T} and Phi_V in structured form; everything else as there. */
+fedrag_status fedrag_scramble_kv_structured(const fedrag_shape* shape, int64_t L_kv,
+                                            const void* K, const void* V,
+                                            const fedrag_structured_key* key_k,
+                                            const fedrag_structured_key* key_v,
+                                            const int32_t* perm_kv, int32_t n_perm,
+                                            void* K_out, void* V_out, void* stream);
+
+/* fedrag_scramble_q with Phi_KQ in structured form. */
+fedrag_status fedrag_scramble_q_structured(const fedrag_shape* shape, int64_t L_q, const void* Q,
+                                           const fedrag_structured_key* key_q, const int32_t* perm_q,
+                                           void* Q_out, void* stream);
+
+/* fedrag_unscramble with Phi_V^{-1} in structured form (fp32 throughout). */
+fedrag_status fedrag_unscramble_structured(const fedrag_shape* shape, int64_t L_q, const float* O_scr,
+                                           const fedrag_structured_key* key_v_inv, const int32_t* perm_q,
+                                           float* O_out, void* stream);
+
 /* inv_out[perm[j]] = j for j in [0, L): the gather array that undoes `perm`.  Device pointers. */
 fedrag_status fedrag_invert_perm(const int32_t* perm, int64_t L, int32_t* inv_out, void* stream);
 

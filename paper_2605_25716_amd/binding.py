@@ -20,12 +20,19 @@ _DTYPES = {torch.float32: F32, torch.bfloat16: BF16, torch.float16: F16}
 
 EXPORTS = ("fedrag_scramble_kv", "fedrag_scramble_q", "fedrag_partial_attn",
            "fedrag_partial_attn_workspace_bytes", "fedrag_lse_merge", "fedrag_unscramble",
+           "fedrag_scramble_kv_structured", "fedrag_scramble_q_structured", "fedrag_unscramble_structured",
            "fedrag_invert_perm", "fedrag_status_string", "fedrag_version")
 
 
 class Shape(ctypes.Structure):
     _fields_ = [("batch", ctypes.c_int32), ("n_q_heads", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32),
                 ("d_head", ctypes.c_int32), ("dtype", ctypes.c_int32)]
+
+
+class StructuredKey(ctypes.Structure):
+    """fedrag_structured_key: host struct of four device pointers, [Hkv, d] each."""
+    _fields_ = [("scale_in", ctypes.c_void_p), ("perm_in", ctypes.c_void_p), ("perm_out", ctypes.c_void_p),
+                ("scale_out", ctypes.c_void_p)]
 
 
 class FedragError(RuntimeError):
@@ -61,12 +68,17 @@ def load() -> ctypes.CDLL:
         lib.fedrag_partial_attn_workspace_bytes.restype = ctypes.c_size_t
         lib.fedrag_lse_merge.argtypes = [sp, i64, i32, f32p, f32p, f32p, f32p, vp]
         lib.fedrag_unscramble.argtypes = [sp, i64, f32p, f32p, vp, f32p, vp]
+        kp = ctypes.POINTER(StructuredKey)
+        lib.fedrag_scramble_kv_structured.argtypes = [sp, i64, vp, vp, kp, kp, vp, i32, vp, vp, vp]
+        lib.fedrag_scramble_q_structured.argtypes = [sp, i64, vp, kp, vp, vp, vp]
+        lib.fedrag_unscramble_structured.argtypes = [sp, i64, f32p, kp, vp, f32p, vp]
         lib.fedrag_invert_perm.argtypes = [vp, i64, vp, vp]
         lib.fedrag_status_string.argtypes = [ctypes.c_int]
         lib.fedrag_status_string.restype = ctypes.c_char_p
         lib.fedrag_version.restype = ctypes.c_int
         for name in ("fedrag_scramble_kv", "fedrag_scramble_q", "fedrag_partial_attn", "fedrag_lse_merge",
-                     "fedrag_unscramble", "fedrag_invert_perm"):
+                     "fedrag_unscramble", "fedrag_invert_perm", "fedrag_scramble_kv_structured",
+                     "fedrag_scramble_q_structured", "fedrag_unscramble_structured"):
             getattr(lib, name).restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -181,6 +193,62 @@ def fedrag_unscramble(O_scr, phi_v_inv, perm_q=None, O_out=None):
     st = load().fedrag_unscramble(ctypes.byref(shape), Lq, _ptr(O_scr), _ptr(phi_v_inv), _ptr(perm_q), _ptr(O_out),
                                   _stream())
     _check(st, "fedrag_unscramble")
+    return O_out
+
+
+def _key(key) -> StructuredKey:
+    """key = (scale_in fp32, perm_in int32, perm_out int32, scale_out fp32), CUDA tensors [Hkv, d]."""
+    a, g1, g2, b = key
+    if a.dtype != torch.float32 or b.dtype != torch.float32 or g1.dtype != torch.int32 or g2.dtype != torch.int32:
+        raise ValueError("structured key: scales are fp32, permutations int32")
+    if not (a.shape == g1.shape == g2.shape == b.shape and a.dim() == 2):
+        raise ValueError("structured key: four [Hkv, d] arrays")
+    return StructuredKey(_ptr(a), _ptr(g1), _ptr(g2), _ptr(b))
+
+
+def fedrag_scramble_kv_structured(K, V, key_k, key_v, perm_kv=None, n_q_heads: Optional[int] = None,
+                                  K_out=None, V_out=None):
+    """fedrag_scramble_kv with Phi_KQ^{-T} and Phi_V given as S1 P1 H P2 S2 factors (Section 4.2)."""
+    B, Hkv, L, d = K.shape
+    if key_k[0].shape != (Hkv, d) or key_v[0].shape != (Hkv, d):
+        raise ValueError("structured key does not match [Hkv, d]")
+    shape = make_shape(B, n_q_heads or Hkv, Hkv, d, K.dtype)
+    K_out = torch.empty_like(K) if K_out is None else K_out
+    V_out = torch.empty_like(V) if V_out is None else V_out
+    n_perm = 0
+    if perm_kv is not None:
+        n_perm = 1 if perm_kv.dim() == 1 else perm_kv.shape[0]
+    kk, kv = _key(key_k), _key(key_v)
+    st = load().fedrag_scramble_kv_structured(ctypes.byref(shape), L, _ptr(K), _ptr(V), ctypes.byref(kk),
+                                              ctypes.byref(kv), _ptr(perm_kv), n_perm, _ptr(K_out), _ptr(V_out),
+                                              _stream())
+    _check(st, "fedrag_scramble_kv_structured")
+    return K_out, V_out
+
+
+def fedrag_scramble_q_structured(Q, key_q, perm_q=None, Q_out=None):
+    B, Hq, Lq, d = Q.shape
+    if key_q[0].dim() != 2 or key_q[0].shape[1] != d:
+        raise ValueError("structured key does not match [Hkv, d]")
+    shape = make_shape(B, Hq, key_q[0].shape[0], d, Q.dtype)
+    Q_out = torch.empty_like(Q) if Q_out is None else Q_out
+    kq = _key(key_q)
+    st = load().fedrag_scramble_q_structured(ctypes.byref(shape), Lq, _ptr(Q), ctypes.byref(kq), _ptr(perm_q),
+                                             _ptr(Q_out), _stream())
+    _check(st, "fedrag_scramble_q_structured")
+    return Q_out
+
+
+def fedrag_unscramble_structured(O_scr, key_v_inv, perm_q=None, O_out=None):
+    B, Hq, Lq, d = O_scr.shape
+    if key_v_inv[0].dim() != 2 or key_v_inv[0].shape[1] != d:
+        raise ValueError("structured key does not match [Hkv, d]")
+    shape = make_shape(B, Hq, key_v_inv[0].shape[0], d, F32)
+    O_out = torch.empty_like(O_scr) if O_out is None else O_out
+    kv = _key(key_v_inv)
+    st = load().fedrag_unscramble_structured(ctypes.byref(shape), Lq, _ptr(O_scr), ctypes.byref(kv), _ptr(perm_q),
+                                             _ptr(O_out), _stream())
+    _check(st, "fedrag_unscramble_structured")
     return O_out
 
 

@@ -41,6 +41,21 @@ bool tensor_elems(int64_t B, int64_t H, int64_t L, int64_t d, int64_t* out) {
 
 fedrag_status dev(hipError_t e) { return e == hipSuccess ? FEDRAG_OK : FEDRAG_ERR_DEVICE; }
 
+fedrag_status check_key(const fedrag_structured_key* k) {
+    if (!k || !k->scale_in || !k->perm_in || !k->perm_out || !k->scale_out) return FEDRAG_ERR_NULL;
+    const uintptr_t bits = reinterpret_cast<uintptr_t>(k->scale_in) | reinterpret_cast<uintptr_t>(k->perm_in) |
+                           reinterpret_cast<uintptr_t>(k->perm_out) | reinterpret_cast<uintptr_t>(k->scale_out);
+    return (bits & 3u) ? FEDRAG_ERR_ALIAS : FEDRAG_OK;
+}
+
+void set_key(RowsJob& j, int i, const fedrag_structured_key* k) {
+    j.structured = true;
+    j.s_in[i] = k->scale_in;
+    j.p_in[i] = k->perm_in;
+    j.p_out[i] = k->perm_out;
+    j.s_out[i] = k->scale_out;
+}
+
 }  // namespace
 
 extern "C" {
@@ -176,6 +191,104 @@ fedrag_status fedrag_unscramble(const fedrag_shape* shape, int64_t L_q, const fl
     j.n_jobs = 1;
     j.X[0] = O_scr; j.Phi[0] = phi_v_inv; j.Y[0] = O_out;
     j.X[1] = O_scr; j.Phi[1] = phi_v_inv; j.Y[1] = O_out;
+    j.perm = perm_q;
+    j.perm_batch_stride = 0;
+    j.BH = (int64_t)shape->batch * shape->n_q_heads;
+    j.H = shape->n_q_heads;
+    j.G = shape->n_q_heads / shape->n_kv_heads;
+    j.L = L_q;
+    j.D = shape->d_head;
+    j.dtype = FEDRAG_F32;
+    j.scatter = true;
+    return dev(launch_rows_transform(j, (hipStream_t)stream));
+}
+
+fedrag_status fedrag_scramble_kv_structured(const fedrag_shape* shape, int64_t L_kv, const void* K, const void* V,
+                                            const fedrag_structured_key* key_k, const fedrag_structured_key* key_v,
+                                            const int32_t* perm_kv, int32_t n_perm, void* K_out, void* V_out,
+                                            void* stream) {
+    fedrag_status st = check_shape(shape, true);
+    if (st != FEDRAG_OK) return st;
+    if (L_kv < 0 || L_kv > INT32_MAX) return FEDRAG_ERR_SHAPE;
+    if (!K || !V || !K_out || !V_out) return FEDRAG_ERR_NULL;
+    if ((st = check_key(key_k)) != FEDRAG_OK || (st = check_key(key_v)) != FEDRAG_OK) return st;
+    if (perm_kv && n_perm != 1 && n_perm != shape->batch) return FEDRAG_ERR_SHAPE;
+    int64_t n;
+    if (!tensor_elems(shape->batch, shape->n_kv_heads, L_kv, shape->d_head, &n)) return FEDRAG_ERR_SHAPE;
+    const size_t bytes = (size_t)n * elem_size(shape->dtype);
+    if (!aligned16(K) || !aligned16(V) || !aligned16(K_out) || !aligned16(V_out) ||
+        (reinterpret_cast<uintptr_t>(perm_kv) & 3u))
+        return FEDRAG_ERR_ALIAS;
+    if (overlaps(K_out, bytes, K, bytes) || overlaps(K_out, bytes, V, bytes) || overlaps(V_out, bytes, K, bytes) ||
+        overlaps(V_out, bytes, V, bytes) || overlaps(K_out, bytes, V_out, bytes))
+        return FEDRAG_ERR_ALIAS;
+    RowsJob j{};
+    j.n_jobs = 2;
+    j.X[0] = K; j.Y[0] = K_out;
+    j.X[1] = V; j.Y[1] = V_out;
+    set_key(j, 0, key_k);
+    set_key(j, 1, key_v);
+    j.perm = perm_kv;
+    j.perm_batch_stride = (perm_kv && n_perm > 1) ? L_kv : 0;
+    j.BH = (int64_t)shape->batch * shape->n_kv_heads;
+    j.H = shape->n_kv_heads;
+    j.G = 1;
+    j.L = L_kv;
+    j.D = shape->d_head;
+    j.dtype = shape->dtype;
+    j.scatter = false;
+    return dev(launch_rows_transform(j, (hipStream_t)stream));
+}
+
+fedrag_status fedrag_scramble_q_structured(const fedrag_shape* shape, int64_t L_q, const void* Q,
+                                           const fedrag_structured_key* key_q, const int32_t* perm_q, void* Q_out,
+                                           void* stream) {
+    fedrag_status st = check_shape(shape, true);
+    if (st != FEDRAG_OK) return st;
+    if (L_q < 0 || L_q > INT32_MAX) return FEDRAG_ERR_SHAPE;
+    if (!Q || !Q_out) return FEDRAG_ERR_NULL;
+    if ((st = check_key(key_q)) != FEDRAG_OK) return st;
+    int64_t n;
+    if (!tensor_elems(shape->batch, shape->n_q_heads, L_q, shape->d_head, &n)) return FEDRAG_ERR_SHAPE;
+    const size_t bytes = (size_t)n * elem_size(shape->dtype);
+    if (!aligned16(Q) || !aligned16(Q_out) || (reinterpret_cast<uintptr_t>(perm_q) & 3u)) return FEDRAG_ERR_ALIAS;
+    if (overlaps(Q_out, bytes, Q, bytes)) return FEDRAG_ERR_ALIAS;
+    RowsJob j{};
+    j.n_jobs = 1;
+    j.X[0] = j.X[1] = Q;
+    j.Y[0] = j.Y[1] = Q_out;
+    set_key(j, 0, key_q);
+    set_key(j, 1, key_q);
+    j.perm = perm_q;
+    j.perm_batch_stride = 0;
+    j.BH = (int64_t)shape->batch * shape->n_q_heads;
+    j.H = shape->n_q_heads;
+    j.G = shape->n_q_heads / shape->n_kv_heads;
+    j.L = L_q;
+    j.D = shape->d_head;
+    j.dtype = shape->dtype;
+    j.scatter = false;
+    return dev(launch_rows_transform(j, (hipStream_t)stream));
+}
+
+fedrag_status fedrag_unscramble_structured(const fedrag_shape* shape, int64_t L_q, const float* O_scr,
+                                           const fedrag_structured_key* key_v_inv, const int32_t* perm_q, float* O_out,
+                                           void* stream) {
+    fedrag_status st = check_shape(shape, false);
+    if (st != FEDRAG_OK) return st;
+    if (L_q < 0 || L_q > INT32_MAX) return FEDRAG_ERR_SHAPE;
+    if (!O_scr || !O_out) return FEDRAG_ERR_NULL;
+    if ((st = check_key(key_v_inv)) != FEDRAG_OK) return st;
+    int64_t n;
+    if (!tensor_elems(shape->batch, shape->n_q_heads, L_q, shape->d_head, &n)) return FEDRAG_ERR_SHAPE;
+    if (!aligned16(O_scr) || !aligned16(O_out) || (reinterpret_cast<uintptr_t>(perm_q) & 3u)) return FEDRAG_ERR_ALIAS;
+    if (overlaps(O_out, (size_t)n * 4, O_scr, (size_t)n * 4)) return FEDRAG_ERR_ALIAS;
+    RowsJob j{};
+    j.n_jobs = 1;
+    j.X[0] = j.X[1] = O_scr;
+    j.Y[0] = j.Y[1] = O_out;
+    set_key(j, 0, key_v_inv);
+    set_key(j, 1, key_v_inv);
     j.perm = perm_q;
     j.perm_batch_stride = 0;
     j.BH = (int64_t)shape->batch * shape->n_q_heads;

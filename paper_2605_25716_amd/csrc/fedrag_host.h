@@ -12,7 +12,12 @@ namespace fedrag {
 struct RowsJob {
     int n_jobs;               // 1 or 2
     const void* X[2];
-    const void* Phi[2];       // [Hkv, D, D]
+    const void* Phi[2];       // dense form: [Hkv, D, D]
+    bool structured;          // true: the matrix is given as S1 P1 H P2 S2 by the four arrays below, [Hkv, D] each
+    const float* s_in[2];
+    const int32_t* p_in[2];
+    const int32_t* p_out[2];
+    const float* s_out[2];
     void* Y[2];
     const int32_t* perm;      // NULL = identity
     int64_t perm_batch_stride;  // 0 (one permutation for all sequences) or L

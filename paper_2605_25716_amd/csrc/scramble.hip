@@ -26,9 +26,22 @@ constexpr int kScrRows = 32;  // rows per wave step (two 16-row MFMA column tile
 
 struct ScrambleJob {
     const void* X;
-    const void* Phi;
+    const void* Phi;       // dense form: [Hkv, D, D]
     void* Y;
+    // structured form (Section 4.2, Phi = S1 P1 H P2 S2), [Hkv, D] each; see structured_entry()
+    const float* s_in;
+    const int32_t* p_in;
+    const int32_t* p_out;
+    const float* s_out;
 };
+
+// Entry (k, n) of S1 P1 Hs P2 with the permutations as gathers and Hs the +-1 Sylvester matrix:
+//   x S1 P1 Hs P2 = sum_k x[k] s_in[k] Hs[p_in^{-1}(k)][p_out[n]],   Hs[i][m] = (-1)^popcount(i & m).
+// The 1/sqrt(d) of the normalised Hadamard matrix and S2 are applied to the fp32 sums afterwards, so that every
+// product in the sums is x[k] times +-s_in[k] and nothing is rounded before the accumulation.
+__device__ __forceinline__ float structured_entry(float s_in_k, int p_in_inv_k, int p_out_n) {
+    return (__builtin_popcount(p_in_inv_k & p_out_n) & 1) ? -s_in_k : s_in_k;
+}
 
 // blockIdx.x = (head * members + member) * b_groups + bg; blockIdx.y selects the job (K or V).
 // The `members` workgroups of one (job, head) share that head's Phi and sweep the sequences b = 0..B-1 together:
@@ -39,7 +52,7 @@ struct ScrambleJob {
 // A ring of NBUF register tile sets keeps NBUF-1 gathered tiles (8 KiB each) in flight per wave behind the LDS
 // staging and the MFMAs (it runs straight through the slab boundaries); the gather indices of a tile are fetched
 // one step before its rows.  Tiles that start past the end of a slab are computed on clamped rows and not stored.
-template <class T, int D>
+template <class T, int D, bool ST>
 __global__ __launch_bounds__(kScrThreads, 1) void scramble_rows_kernel(ScrambleJob job0, ScrambleJob job1,
                                                                        const int32_t* __restrict__ perm,
                                                                        int64_t perm_batch_stride,  // 0 or L
@@ -72,7 +85,21 @@ __global__ __launch_bounds__(kScrThreads, 1) void scramble_rows_kernel(ScrambleJ
     const int bg = blockIdx.x % b_groups;  // this workgroup takes sequences bg, bg + b_groups, ...
 
     // ---- stage Phi^T[n][k] = Phi[k][n] in LDS (once per workgroup) ----
-    {
+    __shared__ int32_t p_in_inv[ST ? D : 1];
+    if (ST) {
+        // structured form: the matrix is S1 P1 Hs P2, generated here from the key (entries +-s_in[k], which the
+        // storage type holds exactly by the caller's contract); indices are masked into range
+        const int32_t* g1 = job.p_in + (int64_t)(h / G) * D;
+        for (int k = tid; k < D; k += kScrThreads) p_in_inv[g1[k] & (D - 1)] = k;
+        __syncthreads();
+        const float* a = job.s_in + (int64_t)(h / G) * D;
+        const int32_t* g2 = job.p_out + (int64_t)(h / G) * D;
+        for (int c = tid; c < D * D; c += kScrThreads) {
+            const int n = c / D;
+            const int k = c % D;
+            lds[n * LDP + k] = T::from_float(structured_entry(a[k], p_in_inv[k], g2[n] & (D - 1)));
+        }
+    } else {
         const elem* P = (const elem*)job.Phi + (int64_t)(h / G) * D * D;
         for (int c = tid; c < D * CH; c += kScrThreads) {
             const int k = c / CH;
@@ -94,6 +121,16 @@ __global__ __launch_bounds__(kScrThreads, 1) void scramble_rows_kernel(ScrambleJ
         for (int ks = 0; ks < KS; ++ks)
             phi[mt][ks] = *(const vec8*)(&lds[(mt * 16 + lr) * LDP + ks * 32 + lq * 8]);
     __syncthreads();  // Phi^T is dead from here on; the buffer becomes the row tiles
+    // structured form: S2 and the Hadamard normalisation, for this lane's output columns 16 mt + 4 lq + r
+    f32x4_t post[ST ? MT : 1];
+    if (ST) {
+        const float* b = job.s_out + (int64_t)(h / G) * D;
+        const float norm = D == 128 ? 0.08838834764831845f : 0.125f;  // 1 / sqrt(D)
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) post[mt][r] = b[mt * 16 + lq * 4 + r] * norm;
+    }
 
     elem* my = lds + wave * (kScrRows * LDP);
 
@@ -160,7 +197,7 @@ __global__ __launch_bounds__(kScrThreads, 1) void scramble_rows_kernel(ScrambleJ
             for (int mt = 0; mt < MT; ++mt) {
                 vec4 o;
 #pragma unroll
-                for (int r = 0; r < 4; ++r) o[r] = T::from_float(acc[mt][r]);
+                for (int r = 0; r < 4; ++r) o[r] = T::from_float(ST ? acc[mt][r] * post[mt][r] : acc[mt][r]);
                 *(vec4*)(&my[(half * 16 + lr) * LDP + mt * 16 + lq * 4]) = o;
             }
         }
@@ -206,7 +243,7 @@ __global__ __launch_bounds__(kScrThreads, 1) void scramble_rows_kernel(ScrambleJ
 constexpr int kF32Threads = 256;
 constexpr int kF32Rows = 32;
 
-template <int D, bool SCATTER>
+template <int D, bool SCATTER, bool ST>
 __global__ __launch_bounds__(kF32Threads) void rows_times_matrix_f32_kernel(ScrambleJob job0, ScrambleJob job1,
                                                                             const int32_t* __restrict__ perm,
                                                                             int64_t perm_batch_stride, int H, int G,
@@ -221,10 +258,25 @@ __global__ __launch_bounds__(kF32Threads) void rows_times_matrix_f32_kernel(Scra
     const int chunk = blockIdx.x % chunks;
     const int b = bh / H;
     const int h = bh % H;
-    const float* P = (const float*)job.Phi + (int64_t)(h / G) * D * D;
     float phi[D];
+    __shared__ int32_t p_in_inv[ST ? D : 1];
+    __shared__ float s_in[ST ? D : 1];
+    if (ST) {  // column c of S1 P1 H P2 S2, generated from the key
+        const int32_t* g1 = job.p_in + (int64_t)(h / G) * D;
+        for (int k = tid; k < D; k += kF32Threads) {
+            p_in_inv[g1[k] & (D - 1)] = k;
+            s_in[k] = job.s_in[(int64_t)(h / G) * D + k];
+        }
+        __syncthreads();
+        const int m = job.p_out[(int64_t)(h / G) * D + c] & (D - 1);
+        const float post = job.s_out[(int64_t)(h / G) * D + c] * (D == 128 ? 0.08838834764831845f : 0.125f);
 #pragma unroll
-    for (int k = 0; k < D; ++k) phi[k] = P[k * D + c];
+        for (int k = 0; k < D; ++k) phi[k] = structured_entry(s_in[k], p_in_inv[k], m) * post;
+    } else {
+        const float* P = (const float*)job.Phi + (int64_t)(h / G) * D * D;
+#pragma unroll
+        for (int k = 0; k < D; ++k) phi[k] = P[k * D + c];
+    }
 
     const float* X = (const float*)job.X + (int64_t)bh * L * D;
     float* Y = (float*)job.Y + (int64_t)bh * L * D;
@@ -268,6 +320,10 @@ __global__ void invert_perm_kernel(const int32_t* __restrict__ perm, int64_t L, 
 // ------------------------------------------------------------------------------------------------ launchers
 static int ceil_div_i64(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
 
+static ScrambleJob device_job(const RowsJob& j, int i) {
+    return ScrambleJob{j.X[i], j.Phi[i], j.Y[i], j.s_in[i], j.p_in[i], j.p_out[i], j.s_out[i]};
+}
+
 template <class T, int D>
 static hipError_t launch_scramble16(const RowsJob& j, hipStream_t stream) {
     const int64_t rows_per_pass = kScrWaves * kScrRows;  // rows one workgroup covers per ring step
@@ -283,9 +339,13 @@ static hipError_t launch_scramble16(const RowsJob& j, hipStream_t stream) {
     if (b_groups < 1) b_groups = 1;
     if (b_groups > B) b_groups = B;
     dim3 grid((unsigned)(j.H * members * b_groups), (unsigned)j.n_jobs);
-    ScrambleJob a{j.X[0], j.Phi[0], j.Y[0]}, b{j.X[1], j.Phi[1], j.Y[1]};
-    hipLaunchKernelGGL((scramble_rows_kernel<T, D>), grid, dim3(kScrThreads), 0, stream, a, b, j.perm,
-                       j.perm_batch_stride, B, j.H, j.G, j.L, members, tiles_per_slab, b_groups);
+    const ScrambleJob a = device_job(j, 0), b = device_job(j, 1);
+    if (j.structured)
+        hipLaunchKernelGGL((scramble_rows_kernel<T, D, true>), grid, dim3(kScrThreads), 0, stream, a, b, j.perm,
+                           j.perm_batch_stride, B, j.H, j.G, j.L, members, tiles_per_slab, b_groups);
+    else
+        hipLaunchKernelGGL((scramble_rows_kernel<T, D, false>), grid, dim3(kScrThreads), 0, stream, a, b, j.perm,
+                           j.perm_batch_stride, B, j.H, j.G, j.L, members, tiles_per_slab, b_groups);
     return hipGetLastError();
 }
 
@@ -299,9 +359,13 @@ static hipError_t launch_rows_f32(const RowsJob& j, hipStream_t stream) {
     if (tpw > 64) tpw = 64;
     const int chunks = ceil_div_i64(tiles, tpw);
     dim3 grid((unsigned)(j.BH * chunks), (unsigned)j.n_jobs);
-    ScrambleJob a{j.X[0], j.Phi[0], j.Y[0]}, b{j.X[1], j.Phi[1], j.Y[1]};
-    hipLaunchKernelGGL((rows_times_matrix_f32_kernel<D, SCATTER>), grid, dim3(kF32Threads), 0, stream, a, b, j.perm,
-                       j.perm_batch_stride, j.H, j.G, j.L, chunks, tpw);
+    const ScrambleJob a = device_job(j, 0), b = device_job(j, 1);
+    if (j.structured)
+        hipLaunchKernelGGL((rows_times_matrix_f32_kernel<D, SCATTER, true>), grid, dim3(kF32Threads), 0, stream, a, b,
+                           j.perm, j.perm_batch_stride, j.H, j.G, j.L, chunks, tpw);
+    else
+        hipLaunchKernelGGL((rows_times_matrix_f32_kernel<D, SCATTER, false>), grid, dim3(kF32Threads), 0, stream, a, b,
+                           j.perm, j.perm_batch_stride, j.H, j.G, j.L, chunks, tpw);
     return hipGetLastError();
 }
 

@@ -79,6 +79,44 @@ def test_scramble_q_and_unscramble_validation(lib):
     assert lib.fedrag_unscramble(ctypes.byref(bad), 4, P(A), P(3 * A), None, P(2 * A), None) == fb.ERR_UNSUPPORTED
 
 
+def test_structured_calls_validation(lib):
+    s = shape()
+    key = fb.StructuredKey(A, 2 * A, 3 * A, 4 * A)
+    kq = ctypes.byref(key)
+    f = lib.fedrag_scramble_kv_structured
+    ok_args = lambda: [ctypes.byref(s), 64, P(5 * A), P(6 * A), kq, kq, P(7 * A), 1, P(8 * A), P(9 * A), None]
+    for i in (0, 2, 3, 4, 5, 8, 9):
+        a = ok_args(); a[i] = None
+        assert f(*a) == fb.ERR_NULL
+    for field in ("scale_in", "perm_in", "perm_out", "scale_out"):
+        bad = fb.StructuredKey(A, 2 * A, 3 * A, 4 * A)
+        setattr(bad, field, None)
+        a = ok_args(); a[5] = ctypes.byref(bad)
+        assert f(*a) == fb.ERR_NULL
+        setattr(bad, field, A + 2)            # misaligned key array
+        assert f(*a) == fb.ERR_ALIAS
+    a = ok_args(); a[1] = -1
+    assert f(*a) == fb.ERR_SHAPE
+    a = ok_args(); a[7] = 3
+    assert f(*a) == fb.ERR_SHAPE
+    a = ok_args(); a[8] = P(5 * A)           # K_out aliases K
+    assert f(*a) == fb.ERR_ALIAS
+    bad = shape(d=96); a = ok_args(); a[0] = ctypes.byref(bad)
+    assert f(*a) == fb.ERR_UNSUPPORTED
+    g = lib.fedrag_scramble_q_structured
+    assert g(ctypes.byref(s), 4, P(A), None, None, P(2 * A), None) == fb.ERR_NULL
+    assert g(ctypes.byref(s), 4, None, kq, None, P(2 * A), None) == fb.ERR_NULL
+    assert g(ctypes.byref(s), 4, P(5 * A), kq, None, P(5 * A), None) == fb.ERR_ALIAS
+    assert g(ctypes.byref(s), -1, P(5 * A), kq, None, P(6 * A), None) == fb.ERR_SHAPE
+    u = lib.fedrag_unscramble_structured
+    assert u(ctypes.byref(s), 4, P(5 * A), None, None, P(6 * A), None) == fb.ERR_NULL
+    assert u(ctypes.byref(s), 4, P(5 * A), kq, P(7 * A + 1), P(6 * A), None) == fb.ERR_ALIAS
+    assert u(ctypes.byref(s), 4, P(5 * A), kq, None, P(5 * A + 16), None) == fb.ERR_ALIAS
+    # zero rows: accepted without touching a device
+    assert g(ctypes.byref(s), 0, P(5 * A), kq, None, P(6 * A), None) == fb.OK
+    assert u(ctypes.byref(s), 0, P(5 * A), kq, None, P(6 * A), None) == fb.OK
+
+
 def test_partial_attn_validation_and_workspace(lib):
     s = shape(B=16, Hq=32, Hkv=8)
     need = lib.fedrag_partial_attn_workspace_bytes(ctypes.byref(s), 1, 8192)

@@ -125,6 +125,30 @@ def test_mixed70b_prefill_shard_full_size(oracle):
     run_fullsize(oracle, W.CONFIGS["mixed70b_prefill"], n_units=1, q_rows_per_head=64, heads_per_unit=2)
 
 
+def test_structured_scramble_kv_full_size(oracle):
+    """The structured-key Enc of one KV shard at the size bench.py times, checked on sampled (sequence, head) units."""
+    cfg = W.CONFIGS["llama8b_decode"]
+    dt = W.torch_dtype(cfg.dtype)
+    d = cfg.d_head
+    _, K, V, _ = shard_on_gpu(cfg)
+    ks = W.make_structured_keys(cfg.n_kv_heads, d, cfg.L_q, cfg.L_kv, 1, seed=cfg.seed, dtype=dt)
+    perm = ks.perm_kv[0]
+    dk = lambda key: tuple(t.to(DEV) for t in key)
+    Ks, Vs = fb.fedrag_scramble_kv_structured(K, V, dk(ks.k), dk(ks.v), perm.to(DEV), n_q_heads=cfg.n_q_heads)
+    torch.cuda.synchronize()
+    assert torch.isfinite(Ks.float()).all() and torch.isfinite(Vs.float()).all()
+    absd = lambda key: (key[0].double().abs()[:, :, None] * key[3].double().abs()[:, None, :] / np.sqrt(d)).numpy()
+    rng = np.random.default_rng(cfg.seed + 23)
+    for _ in range(4):
+        b, g = int(rng.integers(cfg.batch)), int(rng.integers(cfg.n_kv_heads))
+        sub = lambda key: tuple(t[g:g + 1] for t in key)
+        Kp, Vp = K[b:b + 1, g:g + 1].cpu(), V[b:b + 1, g:g + 1].cpu()
+        PT.check_scramble(Ks[b:b + 1, g:g + 1], oracle.structured(Kp, sub(ks.k), perm), Kp, absd(sub(ks.k)), perm, 1, dt,
+                          f"K' unit {(b, g)}")
+        PT.check_scramble(Vs[b:b + 1, g:g + 1], oracle.structured(Vp, sub(ks.v), perm), Vp, absd(sub(ks.v)), perm, 1, dt,
+                          f"V' unit {(b, g)}")
+
+
 def test_merge_and_unscramble_at_decode_size(oracle):
     cfg = W.CONFIGS["llama8b_decode"]
     g = torch.Generator().manual_seed(cfg.seed)
