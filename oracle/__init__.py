@@ -152,6 +152,22 @@ def partial_attn(Qs, Ks, Vs, scale=None):
     return O, lse
 
 
+def local_causal_attn(Q, K, V, scale=None):
+    """The Inquirer's own part (Section 5.3): the Lq queries are the last Lq of the Lk local tokens and each sees
+    itself and everything before it.  Returns (O, lse = ln w) like partial_attn."""
+    Q, K, V = _f64(Q), _f64(K), _f64(V)
+    B, Hq, Lq, d = Q.shape
+    _, Hkv, Lk, _ = K.shape
+    assert K.shape == V.shape and K.shape[0] == B and K.shape[3] == d and Hq % Hkv == 0 and Lk >= Lq
+    if scale is None:
+        scale = 1.0 / np.sqrt(float(d))
+    O = np.empty((B, Hq, Lq, d), np.float64)
+    lse = np.empty((B, Hq, Lq), np.float64)
+    _load().oracle_local_causal_attn(_p(Q), _p(K), _p(V), _c_int(B), _c_int(Hq), _c_int(Hkv),
+                                     _c_i64(Lq), _c_i64(Lk), _c_int(d), _c_dbl(float(scale)), _p(O), _p(lse))
+    return O, lse
+
+
 def lse_merge(O_parts, lses):
     """Aggregation in the log domain.  O_parts [S,...,d], lses [S,...] -> (O [...,d], lse [...])."""
     O_parts, lses = _f64(O_parts), _f64(lses)

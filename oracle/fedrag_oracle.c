@@ -239,6 +239,55 @@ void oracle_partial_attn(const double *Q, const double *K, const double *V,
 }
 
 /* ------------------------------------------------------------------------ */
+/* The Inquirer's own part of a decoder layer's attention (Section 5.3,      */
+/* prefill and decoding phases): the queries of the current input segment    */
+/* against the K, V the Inquirer holds itself, where a token attends only to */
+/* itself and the tokens before it.  The Lq queries are the LAST Lq of the   */
+/* Lk local tokens, so query i sees keys t <= i + (Lk - Lq).  Same outputs   */
+/* as oracle_partial_attn: O as in Section 4.1 and lse = ln w, to be         */
+/* aggregated with the descrambled remote result.  Needs Lk >= Lq.           */
+/* ------------------------------------------------------------------------ */
+void oracle_local_causal_attn(const double *Q, const double *K, const double *V,
+                              int B, int Hq, int Hkv, int64_t Lq, int64_t Lk, int d,
+                              double scale, double *O, double *lse)
+{
+    const int G = Hq / Hkv;
+    const int64_t off = Lk - Lq;
+#pragma omp parallel for collapse(2) schedule(dynamic, 1) num_threads(NTHREADS())
+    for (int b = 0; b < B; ++b) {
+        for (int h = 0; h < Hq; ++h) {
+            const int g = h / G;
+            const double *Qh = Q + ((int64_t)b * Hq + h) * Lq * d;
+            const double *Kg = K + ((int64_t)b * Hkv + g) * Lk * d;
+            const double *Vg = V + ((int64_t)b * Hkv + g) * Lk * d;
+            double *Oh = O + ((int64_t)b * Hq + h) * Lq * d;
+            double *lh = lse + ((int64_t)b * Hq + h) * Lq;
+            double *s = (double *)malloc(sizeof(double) * (size_t)(Lk > 0 ? Lk : 1));
+            for (int64_t i = 0; i < Lq; ++i) {
+                const int64_t n_vis = i + off + 1;  /* keys 0 .. i + off */
+                double m = -INFINITY;
+                for (int64_t t = 0; t < n_vis; ++t) {
+                    double dot = 0.0;
+                    for (int c = 0; c < d; ++c) dot += Qh[i * d + c] * Kg[t * d + c];
+                    s[t] = dot * scale;
+                    if (s[t] > m) m = s[t];
+                }
+                double l = 0.0;
+                for (int c = 0; c < d; ++c) Oh[i * d + c] = 0.0;
+                for (int64_t t = 0; t < n_vis; ++t) {
+                    const double p = exp(s[t] - m);
+                    l += p;
+                    for (int c = 0; c < d; ++c) Oh[i * d + c] += p * Vg[t * d + c];
+                }
+                for (int c = 0; c < d; ++c) Oh[i * d + c] /= l;
+                lh[i] = m + log(l);
+            }
+            free(s);
+        }
+    }
+}
+
+/* ------------------------------------------------------------------------ */
 /* Global aggregation of Section 4.1 with w_i = exp(lse_i), evaluated in the */
 /* log domain: M = max_i lse_i, a_i = exp(lse_i - M),                        */
 /* O = sum a_i O_i / sum a_i, lse = M + ln sum a_i.                          */
