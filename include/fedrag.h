@@ -104,6 +104,29 @@ fedrag_status fedrag_partial_attn(const fedrag_shape* shape, int64_t L_q, int64_
 size_t fedrag_partial_attn_workspace_bytes(const fedrag_shape* shape, int64_t L_q, int64_t L_kv);
 
 /*
+ * The Inquirer's own part of a decoder layer's attention (Section 5.3, prefill and decoding phases): the queries
+ * of the current input segment against the K, V the Inquirer holds itself, in plaintext, where a token attends
+ * to itself and to the tokens before it.  The L_q queries are the LAST L_q of the L_kv local tokens:
+ *     query i sees keys t <= i + (L_kv - L_q);  O_part, lse as in fedrag_partial_attn, over those keys.
+ * The result is aggregated (fedrag_lse_merge) with the Compute Node's result after that has been descrambled
+ * (fedrag_unscramble for the outputs, fedrag_unpermute_lse for their log-sum-exps).
+ * Q : [B,Hq,L_q,d], K, V : [B,Hkv,L_kv,d], dtype storage; L_kv >= L_q (else FEDRAG_ERR_SHAPE).  Other arguments,
+ * workspace rule (with the same sizes) and errors as fedrag_partial_attn.
+ */
+fedrag_status fedrag_local_attn(const fedrag_shape* shape, int64_t L_q, int64_t L_kv,
+                                const void* Q, const void* K, const void* V, float softmax_scale,
+                                float* O_part, float* lse,
+                                void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * The token-permutation part of Dec (Section 4.2, protocol step 3) for the log-sum-exps that travel with the
+ * outputs:  lse_out[b,h,perm_q[i]] = lse_scr[b,h,i]  (perm_q as given to fedrag_scramble_q; NULL copies).
+ * fp32 [B,Hq,L_q] in and out, out of place.  shape->dtype is ignored.
+ */
+fedrag_status fedrag_unpermute_lse(const fedrag_shape* shape, int64_t L_q, const float* lse_scr,
+                                   const int32_t* perm_q, float* lse_out, void* stream);
+
+/*
  * Global aggregation (Section 4.1): sum_i w_i (.) O_i / sum_i w_i with w_i = exp(lse_i), evaluated as
  *     M = max_i lse_i, a_i = exp(lse_i - M), O = sum a_i O_i / sum a_i, lse = M + ln sum a_i.
  * O_parts : fp32 [S,B,Hq,L_q,d], lses : fp32 [S,B,Hq,L_q] -> O_out fp32 [B,Hq,L_q,d], lse_out fp32 [B,Hq,L_q].

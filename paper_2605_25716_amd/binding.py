@@ -21,7 +21,7 @@ _DTYPES = {torch.float32: F32, torch.bfloat16: BF16, torch.float16: F16}
 EXPORTS = ("fedrag_scramble_kv", "fedrag_scramble_q", "fedrag_partial_attn",
            "fedrag_partial_attn_workspace_bytes", "fedrag_lse_merge", "fedrag_unscramble",
            "fedrag_scramble_kv_structured", "fedrag_scramble_q_structured", "fedrag_unscramble_structured",
-           "fedrag_invert_perm", "fedrag_status_string", "fedrag_version")
+           "fedrag_local_attn", "fedrag_unpermute_lse", "fedrag_invert_perm", "fedrag_status_string", "fedrag_version")
 
 
 class Shape(ctypes.Structure):
@@ -64,6 +64,8 @@ def load() -> ctypes.CDLL:
         lib.fedrag_scramble_q.argtypes = [sp, i64, vp, vp, vp, vp, vp]
         lib.fedrag_partial_attn.argtypes = [sp, i64, i64, vp, vp, vp, ctypes.c_float, f32p, f32p, vp,
                                             ctypes.c_size_t, vp]
+        lib.fedrag_local_attn.argtypes = lib.fedrag_partial_attn.argtypes
+        lib.fedrag_unpermute_lse.argtypes = [sp, i64, f32p, vp, f32p, vp]
         lib.fedrag_partial_attn_workspace_bytes.argtypes = [sp, i64, i64]
         lib.fedrag_partial_attn_workspace_bytes.restype = ctypes.c_size_t
         lib.fedrag_lse_merge.argtypes = [sp, i64, i32, f32p, f32p, f32p, f32p, vp]
@@ -78,7 +80,8 @@ def load() -> ctypes.CDLL:
         lib.fedrag_version.restype = ctypes.c_int
         for name in ("fedrag_scramble_kv", "fedrag_scramble_q", "fedrag_partial_attn", "fedrag_lse_merge",
                      "fedrag_unscramble", "fedrag_invert_perm", "fedrag_scramble_kv_structured",
-                     "fedrag_scramble_q_structured", "fedrag_unscramble_structured"):
+                     "fedrag_scramble_q_structured", "fedrag_unscramble_structured", "fedrag_local_attn",
+                     "fedrag_unpermute_lse"):
             getattr(lib, name).restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -171,6 +174,37 @@ def fedrag_partial_attn(Qs, Ks, Vs, softmax_scale: Optional[float] = None, O_par
                                     _ptr(lse), _ptr(workspace), ws_bytes, _stream())
     _check(st, "fedrag_partial_attn")
     return O_part, lse
+
+
+def fedrag_local_attn(Q, K, V, softmax_scale: Optional[float] = None, O_part=None, lse=None, workspace=None):
+    """The Inquirer's own part (Section 5.3): the Lq queries are the last Lq of the L local tokens, each sees itself
+    and what comes before.  Q [B,Hq,Lq,d], K/V [B,Hkv,L,d] plaintext -> fp32 [B,Hq,Lq,d], fp32 [B,Hq,Lq]."""
+    B, Hq, Lq, d = Q.shape
+    Hkv, L = K.shape[1], K.shape[2]
+    shape = make_shape(B, Hq, Hkv, d, Q.dtype)
+    if softmax_scale is None:
+        softmax_scale = float(d) ** -0.5
+    O_part = torch.empty((B, Hq, Lq, d), dtype=torch.float32, device=Q.device) if O_part is None else O_part
+    lse = torch.empty((B, Hq, Lq), dtype=torch.float32, device=Q.device) if lse is None else lse
+    need = int(load().fedrag_partial_attn_workspace_bytes(ctypes.byref(shape), Lq, L)) if Lq == 1 else 0
+    if workspace is None and need > 0:
+        workspace = torch.empty(need, dtype=torch.uint8, device=Q.device)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    st = load().fedrag_local_attn(ctypes.byref(shape), Lq, L, _ptr(Q), _ptr(K) if L > 0 else None,
+                                  _ptr(V) if L > 0 else None, ctypes.c_float(softmax_scale), _ptr(O_part), _ptr(lse),
+                                  _ptr(workspace), ws_bytes, _stream())
+    _check(st, "fedrag_local_attn")
+    return O_part, lse
+
+
+def fedrag_unpermute_lse(lse_scr, perm_q=None, lse_out=None):
+    """lse_out[b,h,perm_q[i]] = lse_scr[b,h,i]: the log-sum-exps back in the query rows' own order."""
+    B, Hq, Lq = lse_scr.shape
+    shape = make_shape(B, Hq, Hq, 128, F32)
+    lse_out = torch.empty_like(lse_scr) if lse_out is None else lse_out
+    st = load().fedrag_unpermute_lse(ctypes.byref(shape), Lq, _ptr(lse_scr), _ptr(perm_q), _ptr(lse_out), _stream())
+    _check(st, "fedrag_unpermute_lse")
+    return lse_out
 
 
 def fedrag_lse_merge(O_parts, lses, n_kv_heads: Optional[int] = None, O_out=None, lse_out=None):

@@ -14,7 +14,7 @@ namespace fedrag {
 template <int D>
 __global__ __launch_bounds__(256) void attn_f32_kernel(const float* __restrict__ Q, const float* __restrict__ K,
                                                        const float* __restrict__ V, int Hq, int Hkv, int64_t Lq,
-                                                       int64_t L, int64_t total_rows, float scale,
+                                                       int64_t Lkv, int causal, int64_t total_rows, float scale,
                                                        float* __restrict__ O, float* __restrict__ lse) {
     constexpr int CPL = D / kWave;  // output columns per lane
     __shared__ float qs[4][D];
@@ -27,8 +27,10 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const float* __restrict__
     const int h = (int)(bh % Hq);
     const int g = h / (Hq / Hkv);
     const float* q = Q + row * D;
-    const float* Kg = K + ((int64_t)b * Hkv + g) * L * D;
-    const float* Vg = V + ((int64_t)b * Hkv + g) * L * D;
+    const float* Kg = K + ((int64_t)b * Hkv + g) * Lkv * D;
+    const float* Vg = V + ((int64_t)b * Hkv + g) * Lkv * D;
+    // keys this row sees: all of them, or (causal) those up to its own position among the last Lq tokens
+    const int64_t L = causal ? (row % Lq) + (Lkv - Lq) + 1 : Lkv;
     for (int c = lane; c < D; c += kWave) qs[wave][c] = q[c];
     wave_lds_fence();
 
@@ -134,17 +136,21 @@ template <int D>
 static hipError_t launch_attn_f32(const AttnProblem& p, hipStream_t stream) {
     const int64_t rows = (int64_t)p.B * p.Hq * p.Lq;
     hipLaunchKernelGGL(attn_f32_kernel<D>, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, stream, (const float*)p.Q,
-                       (const float*)p.K, (const float*)p.V, p.Hq, p.Hkv, p.Lq, p.Lkv, rows, p.scale, p.O, p.lse);
+                       (const float*)p.K, (const float*)p.V, p.Hq, p.Hkv, p.Lq, p.Lkv, p.causal ? 1 : 0, rows, p.scale,
+                       p.O, p.lse);
     return hipGetLastError();
 }
 
-hipError_t launch_partial_attn(const AttnProblem& p, hipStream_t stream) {
+hipError_t launch_partial_attn(const AttnProblem& p_in, hipStream_t stream) {
+    AttnProblem p = p_in;
+    if (p.Lq == 1) p.causal = false;  // a single query at the last position sees every key
     const int64_t rows = (int64_t)p.B * p.Hq * p.Lq;
     if (rows == 0) return hipSuccess;
     if (p.Lkv == 0) return launch_fill_empty(p.O, p.lse, rows, p.D, stream);
     if (p.dtype == FEDRAG_F32) return p.D == 128 ? launch_attn_f32<128>(p, stream) : launch_attn_f32<64>(p, stream);
     if (p.dtype != FEDRAG_BF16 && p.dtype != FEDRAG_F16) return hipErrorInvalidValue;
-    return use_decode_kernel(p.Hq, p.Hkv, p.Lq) ? launch_decode_attn(p, stream) : launch_prefill_attn(p, stream);
+    return (!p.causal && use_decode_kernel(p.Hq, p.Hkv, p.Lq)) ? launch_decode_attn(p, stream)
+                                                               : launch_prefill_attn(p, stream);
 }
 
 }  // namespace fedrag

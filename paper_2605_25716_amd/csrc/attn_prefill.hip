@@ -40,7 +40,9 @@ __device__ __forceinline__ u32x2_t lds_read_tr16(const char* p) {
     return __builtin_bit_cast(u32x2_t, v);
 }
 
-template <class T, int D>
+// CAUSAL: the queries are the last Lq of the L tokens whose K'/V' are given, and query i sees keys 0 .. i + (L - Lq)
+// (Section 5.3: the Inquirer's own part of a decoder layer's attention).
+template <class T, int D, bool CAUSAL>
 __global__ __launch_bounds__(kPreThreads, 1) void prefill_attn_kernel(const typename T::elem* __restrict__ Q,
                                                                       const typename T::elem* __restrict__ K,
                                                                       const typename T::elem* __restrict__ V, int Hq,
@@ -139,7 +141,15 @@ __global__ __launch_bounds__(kPreThreads, 1) void prefill_attn_kernel(const type
         v_off[i] = (4 * lh + s16 / 4) * ROWB + (((chunk % CH) ^ swz) << 4) + 8 * ((s16 % 4) % 2);
     }
 
-    const int n_tiles = (int)((L + kPreK - 1) / kPreK);
+    // keys this workgroup has to visit, and the first tile in which some key is hidden from some row of the
+    // workgroup (past the end of the shard, or - CAUSAL - after the row's own position)
+    const int64_t off = L - Lq;
+    const int64_t q_first = (int64_t)qt * kPreQTile;
+    const int64_t q_last = (q_first + kPreQTile < Lq ? q_first + kPreQTile : Lq) - 1;
+    const int64_t wg_keys = CAUSAL ? (q_last + off + 1 < L ? q_last + off + 1 : L) : L;
+    const int n_tiles = (int)((wg_keys + kPreK - 1) / kPreK);
+    const int t_mask0 = (int)((CAUSAL ? (q_first + off + 1 < L ? q_first + off + 1 : L) : L) / kPreK);
+    const int key_lim = (int)(CAUSAL ? (q_row + off + 1 < L ? q_row + off + 1 : L) : L);  // this lane's row sees keys < key_lim
     f32x16_t S0;      // S^T of the current tile, keys 0..31
     f32x16_t S1[2];   // S1[t & 1]: S^T of tile t, keys 32..63 (kept one iteration longer, see below)
     vec8 P[2][4];     // P[t & 1]: P^T operands of tile t, one per 16-key step
@@ -283,12 +293,12 @@ __global__ __launch_bounds__(kPreThreads, 1) void prefill_attn_kernel(const type
             }
             if (doAB) {  // B1(t); keys past the end of the shard get a score of -inf (also seen by B2(t) later)
                 const int key0 = t * kPreK;
-                if (key0 + kPreK > (int)L) {  // ragged last tile
+                if (t >= t_mask0) {  // ragged last tile, or tiles that reach past a row's own position
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {
                         const int key = key0 + 8 * (r / 4) + 4 * lh + (r % 4);
-                        if (key >= (int)L) S0[r] = -INFINITY;
-                        if (key + 32 >= (int)L) S1[p][r] = -INFINITY;
+                        if (key >= key_lim) S0[r] = -INFINITY;
+                        if (key + 32 >= key_lim) S1[p][r] = -INFINITY;
                     }
                 }
                 float mx = S0[0];
@@ -327,11 +337,12 @@ __global__ __launch_bounds__(kPreThreads, 1) void prefill_attn_kernel(const type
     alph[0] = alph[1] = 1.0f;
     __syncthreads();
 
-    // iterations t = 0 .. n_tiles; the steady-state ones (1 <= t, t + 1 < n_tiles) run with every stage on
+    // iterations t = 0 .. n_tiles; the steady-state ones (1 <= t, t + 1 < n_tiles, no hidden keys) run with every
+    // stage on and without the masking code
     iteration(0, even, false, true, n_tiles > 1, true);
     __syncthreads();
     int t = 1;
-    for (; t + 2 < n_tiles; t += 2) {
+    for (; t + 2 < n_tiles && t + 1 < t_mask0; t += 2) {
         iteration(t, odd, true, true, true, false);
         __syncthreads();
         iteration(t + 1, even, true, true, true, false);
@@ -360,7 +371,7 @@ __global__ __launch_bounds__(kPreThreads, 1) void prefill_attn_kernel(const type
     }
 }
 
-template <class T, int D>
+template <class T, int D, bool CAUSAL>
 static hipError_t launch_prefill_t(const AttnProblem& p, hipStream_t stream) {
     typedef typename T::elem elem;
     const float scale_log2 = p.scale * kLog2e;
@@ -368,16 +379,21 @@ static hipError_t launch_prefill_t(const AttnProblem& p, hipStream_t stream) {
     const int n_units = p.B * p.Hkv;
     const int per_unit = (p.Hq / p.Hkv) * q_tiles;
     const int64_t grid = (int64_t)8 * ((n_units + 7) / 8) * per_unit;
-    hipLaunchKernelGGL((prefill_attn_kernel<T, D>), dim3((unsigned)grid), dim3(kPreThreads), 0,
+    hipLaunchKernelGGL((prefill_attn_kernel<T, D, CAUSAL>), dim3((unsigned)grid), dim3(kPreThreads), 0,
                        stream, (const elem*)p.Q, (const elem*)p.K, (const elem*)p.V, p.Hq, p.Hkv, p.Lq, p.Lkv, q_tiles,
                        n_units, scale_log2, p.O, p.lse);
     return hipGetLastError();
 }
 
+template <class T>
+static hipError_t launch_prefill_d(const AttnProblem& p, hipStream_t stream) {
+    if (p.causal)
+        return p.D == 128 ? launch_prefill_t<T, 128, true>(p, stream) : launch_prefill_t<T, 64, true>(p, stream);
+    return p.D == 128 ? launch_prefill_t<T, 128, false>(p, stream) : launch_prefill_t<T, 64, false>(p, stream);
+}
+
 hipError_t launch_prefill_attn(const AttnProblem& p, hipStream_t stream) {
-    if (p.dtype == FEDRAG_BF16)
-        return p.D == 128 ? launch_prefill_t<BF16, 128>(p, stream) : launch_prefill_t<BF16, 64>(p, stream);
-    return p.D == 128 ? launch_prefill_t<F16, 128>(p, stream) : launch_prefill_t<F16, 64>(p, stream);
+    return p.dtype == FEDRAG_BF16 ? launch_prefill_d<BF16>(p, stream) : launch_prefill_d<F16>(p, stream);
 }
 
 }  // namespace fedrag

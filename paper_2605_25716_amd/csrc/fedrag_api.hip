@@ -157,6 +157,54 @@ fedrag_status fedrag_partial_attn(const fedrag_shape* shape, int64_t L_q, int64_
     return dev(launch_partial_attn(p, (hipStream_t)stream));
 }
 
+fedrag_status fedrag_local_attn(const fedrag_shape* shape, int64_t L_q, int64_t L_kv, const void* Q, const void* K,
+                                const void* V, float softmax_scale, float* O_part, float* lse, void* workspace,
+                                size_t workspace_bytes, void* stream) {
+    fedrag_status st = check_shape(shape, true);
+    if (st != FEDRAG_OK) return st;
+    if (L_q < 0 || L_kv < L_q || L_kv > INT32_MAX) return FEDRAG_ERR_SHAPE;  // the queries are among the local tokens
+    if (!Q || !O_part || !lse) return FEDRAG_ERR_NULL;
+    if (L_kv > 0 && (!K || !V)) return FEDRAG_ERR_NULL;
+    int64_t nq, nk;
+    if (!tensor_elems(shape->batch, shape->n_q_heads, L_q, shape->d_head, &nq) ||
+        !tensor_elems(shape->batch, shape->n_kv_heads, L_kv, shape->d_head, &nk))
+        return FEDRAG_ERR_SHAPE;
+    if (!(softmax_scale > 0.0f) || softmax_scale - softmax_scale != 0.0f) return FEDRAG_ERR_SHAPE;  // finite, > 0
+    if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O_part) ||
+        (reinterpret_cast<uintptr_t>(lse) & 3u) || !aligned16(workspace))
+        return FEDRAG_ERR_ALIAS;
+    // only a single query per sequence (decoding) can take the KV-split path that needs the workspace
+    const size_t need = L_q == 1 ? attn_workspace_bytes(shape->batch, shape->n_q_heads, shape->n_kv_heads,
+                                                        shape->d_head, shape->dtype, L_q, L_kv)
+                                 : 0;
+    if (need > 0 && (!workspace || workspace_bytes < need)) return FEDRAG_ERR_WORKSPACE;
+    AttnProblem p{};
+    p.B = shape->batch; p.Hq = shape->n_q_heads; p.Hkv = shape->n_kv_heads; p.D = shape->d_head;
+    p.dtype = shape->dtype;
+    p.Lq = L_q; p.Lkv = L_kv;
+    p.Q = Q; p.K = K; p.V = V;
+    p.scale = softmax_scale;
+    p.causal = true;
+    p.O = O_part; p.lse = lse;
+    p.workspace = workspace; p.workspace_bytes = workspace_bytes;
+    return dev(launch_partial_attn(p, (hipStream_t)stream));
+}
+
+fedrag_status fedrag_unpermute_lse(const fedrag_shape* shape, int64_t L_q, const float* lse_scr, const int32_t* perm_q,
+                                   float* lse_out, void* stream) {
+    fedrag_status st = check_shape(shape, false);
+    if (st != FEDRAG_OK) return st;
+    if (L_q < 0 || L_q > INT32_MAX) return FEDRAG_ERR_SHAPE;
+    if (!lse_scr || !lse_out) return FEDRAG_ERR_NULL;
+    const int64_t n_bh = (int64_t)shape->batch * shape->n_q_heads;
+    if (L_q != 0 && n_bh > INT64_MAX / 8 / L_q) return FEDRAG_ERR_SHAPE;
+    if ((reinterpret_cast<uintptr_t>(lse_scr) | reinterpret_cast<uintptr_t>(lse_out) |
+         reinterpret_cast<uintptr_t>(perm_q)) & 3u)
+        return FEDRAG_ERR_ALIAS;
+    if (overlaps(lse_out, (size_t)(n_bh * L_q) * 4, lse_scr, (size_t)(n_bh * L_q) * 4)) return FEDRAG_ERR_ALIAS;
+    return dev(launch_scatter_rows_f32(lse_scr, perm_q, n_bh, L_q, lse_out, (hipStream_t)stream));
+}
+
 fedrag_status fedrag_lse_merge(const fedrag_shape* shape, int64_t L_q, int32_t n_shards, const float* O_parts,
                                const float* lses, float* O_out, float* lse_out, void* stream) {
     fedrag_status st = check_shape(shape, false);

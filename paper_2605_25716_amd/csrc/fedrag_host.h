@@ -38,6 +38,7 @@ struct AttnProblem {
     int64_t Lq, Lkv;
     const void *Q, *K, *V;
     float scale;
+    bool causal;  // the Lq queries are the last Lq of the Lkv tokens and see nothing after themselves
     float* O;     // [B,Hq,Lq,D]
     float* lse;   // [B,Hq,Lq]
     void* workspace;
@@ -62,5 +63,8 @@ hipError_t launch_lse_merge(const float* O_parts, const float* lses, int S, int6
                             hipStream_t stream);
 // O = 0, lse = -inf for `rows` rows (a shard with no keys).
 hipError_t launch_fill_empty(float* O, float* lse, int64_t rows, int D, hipStream_t stream);
+// out[bh, perm[i]] = in[bh, i] for n_bh rows of L values each (perm NULL = copy).
+hipError_t launch_scatter_rows_f32(const float* in, const int32_t* perm, int64_t n_bh, int64_t L, float* out,
+                                   hipStream_t stream);
 
 }  // namespace fedrag

@@ -74,4 +74,24 @@ hipError_t launch_fill_empty(float* O, float* lse, int64_t rows, int D, hipStrea
     return hipGetLastError();
 }
 
+// out[bh, perm[i]] = in[bh, i]: the log-sum-exps of permuted query rows put back in the rows' own order (the
+// token-permutation part of Dec, Section 4.2, for the per-row scalar that travels with the output).
+__global__ void scatter_rows_f32_kernel(const float* __restrict__ in, const int32_t* __restrict__ perm, int64_t L,
+                                        int64_t total, float* __restrict__ out) {
+    const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= total) return;
+    const int64_t bh = e / L, i = e % L;
+    const int64_t dst = perm ? (int64_t)perm[i] : i;
+    out[bh * L + dst] = in[e];
+}
+
+hipError_t launch_scatter_rows_f32(const float* in, const int32_t* perm, int64_t n_bh, int64_t L, float* out,
+                                   hipStream_t stream) {
+    const int64_t total = n_bh * L;
+    if (total == 0) return hipSuccess;
+    hipLaunchKernelGGL(scatter_rows_f32_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, in, perm,
+                       L, total, out);
+    return hipGetLastError();
+}
+
 }  // namespace fedrag

@@ -10,6 +10,9 @@ scramble, 16-bit storage: the kernel accumulates the d exact products of a row i
                  bounded by d * 2^-24 * sum_k |x_k Phi_kj| <= 1e-5 * sum_k |x_k Phi_kj| for d <= 128:
                      |gpu - round(oracle)| <= ulp_storage(oracle) + 2e-5 * sum_k |x_k| |Phi_kj|
                  and at least 97 % of the elements must match bit for bit.
+16-bit path on plaintext V (the Inquirer's local attention; outlier channels not spread by Phi, |v| up to ~80):
+                 the probabilities enter the second product in the storage type (relative rounding 2^-9 bf16), so
+                 the output bound scales with the values: 2e-2 * max(1, max|V| / 8).  lse bound unchanged.
 Index work     : bit-exact.
 """
 import numpy as np
@@ -45,14 +48,16 @@ def max_abs(got, ref):
     return float(np.abs(got[fin] - ref[fin]).max()) if fin.any() else 0.0
 
 
-def check_attn(got_O, got_lse, ref_O, ref_lse, dtype, what=""):
+def check_attn(got_O, got_lse, ref_O, ref_lse, dtype, what="", v_absmax=None):
+    """v_absmax: max |V| when V is plaintext with concentrated outlier channels (scales the 16-bit output bound)."""
     if dtype == torch.float32:
         eo, el = rel_normwise(got_O, ref_O), rel_normwise(got_lse, ref_lse)
         assert eo <= TOL_F32_REL, f"{what}: O rel err {eo:.3e}"
         assert el <= TOL_F32_REL, f"{what}: lse rel err {el:.3e}"
     else:
         eo, el = max_abs(got_O, ref_O), max_abs(got_lse, ref_lse)
-        assert eo <= TOL_16_OUT_ABS, f"{what}: O abs err {eo:.3e}"
+        tol_o = TOL_16_OUT_ABS * (1.0 if v_absmax is None else max(1.0, float(v_absmax) / 8.0))
+        assert eo <= tol_o, f"{what}: O abs err {eo:.3e} > {tol_o:.3e}"
         assert el <= TOL_16_LSE_ABS, f"{what}: lse abs err {el:.3e}"
     return eo, el
 

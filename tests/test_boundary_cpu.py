@@ -117,6 +117,32 @@ def test_structured_calls_validation(lib):
     assert u(ctypes.byref(s), 0, P(5 * A), kq, None, P(6 * A), None) == fb.OK
 
 
+def test_local_attn_and_unpermute_lse_validation(lib):
+    s = shape()
+    f = lib.fedrag_local_attn
+    ok_args = lambda: [ctypes.byref(s), 64, 256, P(A), P(2 * A), P(3 * A), ctypes.c_float(0.1), P(4 * A), P(5 * A),
+                       None, 0, None]
+    for i in (0, 3, 4, 5, 7, 8):
+        a = ok_args(); a[i] = None
+        assert f(*a) == fb.ERR_NULL
+    a = ok_args(); a[1] = 300                 # more queries than local tokens
+    assert f(*a) == fb.ERR_SHAPE
+    a = ok_args(); a[6] = ctypes.c_float(0.0)
+    assert f(*a) == fb.ERR_SHAPE
+    a = ok_args(); a[3] = P(A + 8)
+    assert f(*a) == fb.ERR_ALIAS
+    a = ok_args(); a[1] = 1; a[2] = 1 << 20   # one decoding query over a long local cache: split path, no workspace
+    assert f(*a) == fb.ERR_WORKSPACE
+    a = ok_args(); a[1] = 0; a[2] = 0
+    assert f(*a) == fb.OK
+    u = lib.fedrag_unpermute_lse
+    assert u(ctypes.byref(s), 4, None, None, P(A), None) == fb.ERR_NULL
+    assert u(ctypes.byref(s), 4, P(A), None, P(A), None) == fb.ERR_ALIAS
+    assert u(ctypes.byref(s), 4, P(A), P(3 * A + 2), P(2 * A), None) == fb.ERR_ALIAS
+    assert u(ctypes.byref(s), -1, P(A), None, P(2 * A), None) == fb.ERR_SHAPE
+    assert u(ctypes.byref(s), 0, P(A), None, P(2 * A), None) == fb.OK
+
+
 def test_partial_attn_validation_and_workspace(lib):
     s = shape(B=16, Hq=32, Hkv=8)
     need = lib.fedrag_partial_attn_workspace_bytes(ctypes.byref(s), 1, 8192)
