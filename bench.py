@@ -173,6 +173,31 @@ def structured_leg(torch, W, fb, g, dev, steps, warmup):
             "GB/s": round(gbs, 1), "frac_hbm": round(gbs / HBM_PEAK_GBS, 4)}
 
 
+def local_attn_leg(torch, W, fb, dev, steps, warmup):
+    """The Inquirer's own part of a segment's attention: 4096 plaintext tokens attending to themselves and their
+    predecessors, Llama-3-8B head shape.  Counted flops: 4 d Hq Lq (Lq + 1) / 2 (visible pairs only)."""
+    B, Hq, Hkv, d, L = 1, 32, 8, 128, 4096
+    dt = torch.bfloat16
+    mk = lambda H, tid: W.activations(B, H, L, d, seed=W.BASE_SEED + 6, tensor_id=tid, outliers=True, outlier_id=tid,
+                                      dtype=dt, device=dev)
+    Q, K, V = mk(Hq, W.TID_Q), mk(Hkv, W.TID_K), mk(Hkv, W.TID_V)
+    O = torch.empty((B, Hq, L, d), dtype=torch.float32, device=dev)
+    lse = torch.empty((B, Hq, L), dtype=torch.float32, device=dev)
+    for _ in range(warmup):
+        fb.fedrag_local_attn(Q, K, V, None, O_part=O, lse=lse)
+    torch.cuda.synchronize()
+    timer = CallTimer(torch)
+    for _ in range(steps):
+        timer.run("local_attn", lambda: fb.fedrag_local_attn(Q, K, V, None, O_part=O, lse=lse))
+    torch.cuda.synchronize()
+    t = timer.summary()["local_attn"]
+    flop = 4.0 * d * Hq * B * (L * (L + 1) / 2)
+    tflops = flop / (t["avg_us"] * 1e-6) / 1e12
+    return {"workload": "local_attn: B1 Hq32 Hkv8 d128, 4096-token segment, bf16", "flop": flop,
+            "avg_us": round(t["avg_us"], 2), "value": round(tflops, 1), "unit": "TFLOP/s",
+            "frac_mfma": round(tflops / MFMA_BF16_PEAK_TFLOPS, 4)}
+
+
 def prefill_leg(torch, W, fb, dev, steps, warmup):
     """RAG prefill: partial_attn alone, 2048 queries x 16384 keys, 32/8 heads, d 128, bf16."""
     cfg = W.CONFIGS["rag_prefill"]
@@ -318,6 +343,7 @@ def main():
     line["frac_hbm"] = round(line["value"] / HBM_PEAK_GBS, 4)
     line["structured"] = structured_leg(torch, W, fb, g, dev, args.steps, args.warmup)
     if not args.no_prefill:
+        line["local_attn"] = local_attn_leg(torch, W, fb, dev, max(5, args.steps // 2), args.warmup)
         line["prefill"] = prefill_leg(torch, W, fb, dev, max(5, args.steps // 2), args.warmup)
     if not args.no_cpu:
         line["cpu_baseline"] = cpu_leg(torch, W, g, args.cpu_shards)

@@ -72,7 +72,8 @@ __global__ __launch_bounds__(kPreThreads, 1) void prefill_attn_kernel(const type
     if (unit >= n_units) return;
     const int w_in_unit = slot % per_unit;
     const int hg = w_in_unit / q_tiles;
-    const int qt = w_in_unit % q_tiles;
+    // CAUSAL: later query tiles visit more keys; hand them out first so the short ones fill the tail of the launch
+    const int qt = CAUSAL ? q_tiles - 1 - w_in_unit % q_tiles : w_in_unit % q_tiles;
     const int b = unit / Hkv;
     const int g = unit % Hkv;
     const int h = g * G + hg;
