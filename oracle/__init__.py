@@ -152,6 +152,23 @@ def partial_attn(Qs, Ks, Vs, scale=None):
     return O, lse
 
 
+def partial_attn_varlen(Qs, Ks, Vs, kv_lens, scale=None):
+    """partial_attn over a padded batch: sequence b attends to its first kv_lens[b] keys (Section 5.2 workload)."""
+    Qs, Ks, Vs = _f64(Qs), _f64(Ks), _f64(Vs)
+    B, Hq, Lq, d = Qs.shape
+    _, Hkv, Lk, _ = Ks.shape
+    kv_lens = np.ascontiguousarray(_i32(kv_lens))
+    assert Ks.shape == Vs.shape and Ks.shape[0] == B and Ks.shape[3] == d and Hq % Hkv == 0
+    assert kv_lens.shape == (B,) and kv_lens.min() >= 0 and kv_lens.max() <= Lk
+    if scale is None:
+        scale = 1.0 / np.sqrt(float(d))
+    O = np.empty((B, Hq, Lq, d), np.float64)
+    lse = np.empty((B, Hq, Lq), np.float64)
+    _load().oracle_partial_attn_varlen(_p(Qs), _p(Ks), _p(Vs), _p(kv_lens), _c_int(B), _c_int(Hq), _c_int(Hkv),
+                                       _c_i64(Lq), _c_i64(Lk), _c_int(d), _c_dbl(float(scale)), _p(O), _p(lse))
+    return O, lse
+
+
 def local_causal_attn(Q, K, V, scale=None):
     """The Inquirer's own part (Section 5.3): the Lq queries are the last Lq of the Lk local tokens and each sees
     itself and everything before it.  Returns (O, lse = ln w) like partial_attn."""

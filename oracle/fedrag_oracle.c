@@ -239,6 +239,56 @@ void oracle_partial_attn(const double *Q, const double *K, const double *V,
 }
 
 /* ------------------------------------------------------------------------ */
+/* A batch of sequences of unequal length (Section 5.2: the re-ranker scores */
+/* ten query-document pairs, each its own sequence), stored padded to Lk     */
+/* rows: sequence b attends to its first kv_lens[b] keys only, as            */
+/* oracle_partial_attn does over a shard of that length (0 keys: O = 0,      */
+/* lse = -inf).                                                              */
+/* ------------------------------------------------------------------------ */
+void oracle_partial_attn_varlen(const double *Q, const double *K, const double *V, const int32_t *kv_lens,
+                                int B, int Hq, int Hkv, int64_t Lq, int64_t Lk, int d,
+                                double scale, double *O, double *lse)
+{
+    const int G = Hq / Hkv;
+#pragma omp parallel for collapse(2) schedule(dynamic, 1) num_threads(NTHREADS())
+    for (int b = 0; b < B; ++b) {
+        for (int h = 0; h < Hq; ++h) {
+            const int g = h / G;
+            const int64_t n = kv_lens[b];
+            const double *Qh = Q + ((int64_t)b * Hq + h) * Lq * d;
+            const double *Kg = K + ((int64_t)b * Hkv + g) * Lk * d;
+            const double *Vg = V + ((int64_t)b * Hkv + g) * Lk * d;
+            double *Oh = O + ((int64_t)b * Hq + h) * Lq * d;
+            double *lh = lse + ((int64_t)b * Hq + h) * Lq;
+            double *s = (double *)malloc(sizeof(double) * (size_t)(n > 0 ? n : 1));
+            for (int64_t i = 0; i < Lq; ++i) {
+                for (int c = 0; c < d; ++c) Oh[i * d + c] = 0.0;
+                if (n == 0) {
+                    lh[i] = -INFINITY;
+                    continue;
+                }
+                double m = -INFINITY;
+                for (int64_t t = 0; t < n; ++t) {
+                    double dot = 0.0;
+                    for (int c = 0; c < d; ++c) dot += Qh[i * d + c] * Kg[t * d + c];
+                    s[t] = dot * scale;
+                    if (s[t] > m) m = s[t];
+                }
+                double l = 0.0;
+                for (int64_t t = 0; t < n; ++t) {
+                    const double p = exp(s[t] - m);
+                    l += p;
+                    for (int c = 0; c < d; ++c) Oh[i * d + c] += p * Vg[t * d + c];
+                }
+                for (int c = 0; c < d; ++c) Oh[i * d + c] /= l;
+                lh[i] = m + log(l);
+            }
+            free(s);
+        }
+    }
+}
+
+/* ------------------------------------------------------------------------ */
 /* The Inquirer's own part of a decoder layer's attention (Section 5.3,      */
 /* prefill and decoding phases): the queries of the current input segment    */
 /* against the K, V the Inquirer holds itself, where a token attends only to */
