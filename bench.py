@@ -198,6 +198,35 @@ def local_attn_leg(torch, W, fb, dev, steps, warmup):
             "frac_mfma": round(tflops / MFMA_BF16_PEAK_TFLOPS, 4)}
 
 
+def rerank_leg(torch, W, fb, dev, steps, warmup):
+    """Re-ranking shape (Section 7.1: 10 candidate documents): 10 query-document pairs of unequal length, 16 heads of
+    64 channels, bidirectional attention of every token of a pair over the pair, padded to 1024 tokens."""
+    B, H, d, Lmax = 10, 16, 64, 1024
+    lens = [1024, 896, 777, 640, 512, 512, 400, 333, 256, 130]
+    dt = torch.bfloat16
+    mk = lambda tid: W.activations(B, H, Lmax, d, seed=W.BASE_SEED + 7, tensor_id=tid, outliers=True, outlier_id=tid,
+                                   dtype=dt, device=dev)
+    keys = W.make_keys(H, d, Lmax, Lmax, 1, seed=W.BASE_SEED + 7, dtype=dt, permute_q=False)
+    Qs = fb.fedrag_scramble_q(mk(W.TID_Q), keys.phi_q.to(dev), None)
+    Ks, Vs = fb.fedrag_scramble_kv(mk(W.TID_K), mk(W.TID_V), keys.phi_k.to(dev), keys.phi_v.to(dev), None)
+    kv = torch.tensor(lens, dtype=torch.int32, device=dev)
+    O = torch.empty((B, H, Lmax, d), dtype=torch.float32, device=dev)
+    lse = torch.empty((B, H, Lmax), dtype=torch.float32, device=dev)
+    call = lambda: fb.fedrag_partial_attn_varlen(Qs, Ks, Vs, kv, None, O_part=O, lse=lse)
+    for _ in range(warmup):
+        call()
+    torch.cuda.synchronize()
+    timer = CallTimer(torch)
+    for _ in range(steps):
+        timer.run("rerank", call)
+    torch.cuda.synchronize()
+    t = timer.summary()["rerank"]
+    flop = sum(4.0 * n * n * d * H for n in lens)   # real pairs only: n queries x n keys
+    return {"workload": "rerank: 10 pairs of 130..1024 tokens padded to 1024, 16 heads x 64, bf16, bidirectional",
+            "flop_valid_pairs": flop, "avg_us": round(t["avg_us"], 2),
+            "value": round(flop / (t["avg_us"] * 1e-6) / 1e12, 1), "unit": "TFLOP/s"}
+
+
 def prefill_leg(torch, W, fb, dev, steps, warmup):
     """RAG prefill: partial_attn alone, 2048 queries x 16384 keys, 32/8 heads, d 128, bf16."""
     cfg = W.CONFIGS["rag_prefill"]
@@ -343,6 +372,7 @@ def main():
     line["frac_hbm"] = round(line["value"] / HBM_PEAK_GBS, 4)
     line["structured"] = structured_leg(torch, W, fb, g, dev, args.steps, args.warmup)
     if not args.no_prefill:
+        line["rerank"] = rerank_leg(torch, W, fb, dev, max(5, args.steps // 2), args.warmup)
         line["local_attn"] = local_attn_leg(torch, W, fb, dev, max(5, args.steps // 2), args.warmup)
         line["prefill"] = prefill_leg(torch, W, fb, dev, max(5, args.steps // 2), args.warmup)
     if not args.no_cpu:

@@ -104,6 +104,21 @@ fedrag_status fedrag_partial_attn(const fedrag_shape* shape, int64_t L_q, int64_
 size_t fedrag_partial_attn_workspace_bytes(const fedrag_shape* shape, int64_t L_q, int64_t L_kv);
 
 /*
+ * fedrag_partial_attn over a batch of sequences of unequal length stored padded to L_kv rows (Section 5.2: the
+ * re-ranker scores several query-document pairs at once, each a sequence of its own): sequence b attends to its
+ * first kv_lens[b] keys only; rows of Ks, Vs past that are never used in the result and may hold anything.
+ * kv_lens : int32 [B], DEVICE memory, 0 <= kv_lens[b] <= L_kv (values outside are clamped into that range);
+ * a sequence with 0 keys returns O_part = 0, lse = -inf.  All L_q query rows of every sequence are computed
+ * (padding query rows give finite, meaningless rows).  Everything else, including the workspace size for
+ * (L_q, L_kv), as fedrag_partial_attn.
+ */
+fedrag_status fedrag_partial_attn_varlen(const fedrag_shape* shape, int64_t L_q, int64_t L_kv,
+                                         const void* Qs, const void* Ks, const void* Vs,
+                                         const int32_t* kv_lens, float softmax_scale,
+                                         float* O_part, float* lse,
+                                         void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * The Inquirer's own part of a decoder layer's attention (Section 5.3, prefill and decoding phases): the queries
  * of the current input segment against the K, V the Inquirer holds itself, in plaintext, where a token attends
  * to itself and to the tokens before it.  The L_q queries are the LAST L_q of the L_kv local tokens:

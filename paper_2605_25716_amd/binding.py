@@ -21,7 +21,7 @@ _DTYPES = {torch.float32: F32, torch.bfloat16: BF16, torch.float16: F16}
 EXPORTS = ("fedrag_scramble_kv", "fedrag_scramble_q", "fedrag_partial_attn",
            "fedrag_partial_attn_workspace_bytes", "fedrag_lse_merge", "fedrag_unscramble",
            "fedrag_scramble_kv_structured", "fedrag_scramble_q_structured", "fedrag_unscramble_structured",
-           "fedrag_local_attn", "fedrag_unpermute_lse", "fedrag_invert_perm", "fedrag_status_string", "fedrag_version")
+           "fedrag_local_attn", "fedrag_unpermute_lse", "fedrag_partial_attn_varlen", "fedrag_invert_perm", "fedrag_status_string", "fedrag_version")
 
 
 class Shape(ctypes.Structure):
@@ -65,6 +65,8 @@ def load() -> ctypes.CDLL:
         lib.fedrag_partial_attn.argtypes = [sp, i64, i64, vp, vp, vp, ctypes.c_float, f32p, f32p, vp,
                                             ctypes.c_size_t, vp]
         lib.fedrag_local_attn.argtypes = lib.fedrag_partial_attn.argtypes
+        lib.fedrag_partial_attn_varlen.argtypes = [sp, i64, i64, vp, vp, vp, vp, ctypes.c_float, f32p, f32p, vp,
+                                                   ctypes.c_size_t, vp]
         lib.fedrag_unpermute_lse.argtypes = [sp, i64, f32p, vp, f32p, vp]
         lib.fedrag_partial_attn_workspace_bytes.argtypes = [sp, i64, i64]
         lib.fedrag_partial_attn_workspace_bytes.restype = ctypes.c_size_t
@@ -81,7 +83,7 @@ def load() -> ctypes.CDLL:
         for name in ("fedrag_scramble_kv", "fedrag_scramble_q", "fedrag_partial_attn", "fedrag_lse_merge",
                      "fedrag_unscramble", "fedrag_invert_perm", "fedrag_scramble_kv_structured",
                      "fedrag_scramble_q_structured", "fedrag_unscramble_structured", "fedrag_local_attn",
-                     "fedrag_unpermute_lse"):
+                     "fedrag_unpermute_lse", "fedrag_partial_attn_varlen"):
             getattr(lib, name).restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -173,6 +175,29 @@ def fedrag_partial_attn(Qs, Ks, Vs, softmax_scale: Optional[float] = None, O_par
                                     _ptr(Vs) if L > 0 else None, ctypes.c_float(softmax_scale), _ptr(O_part),
                                     _ptr(lse), _ptr(workspace), ws_bytes, _stream())
     _check(st, "fedrag_partial_attn")
+    return O_part, lse
+
+
+def fedrag_partial_attn_varlen(Qs, Ks, Vs, kv_lens, softmax_scale: Optional[float] = None, O_part=None, lse=None,
+                               workspace=None):
+    """fedrag_partial_attn over a padded batch: sequence b attends to its first kv_lens[b] keys.  kv_lens int32 [B]."""
+    B, Hq, Lq, d = Qs.shape
+    Hkv, L = Ks.shape[1], Ks.shape[2]
+    if kv_lens.dtype != torch.int32 or kv_lens.shape != (B,):
+        raise ValueError("kv_lens: int32 [B]")
+    shape = make_shape(B, Hq, Hkv, d, Qs.dtype)
+    if softmax_scale is None:
+        softmax_scale = float(d) ** -0.5
+    O_part = torch.empty((B, Hq, Lq, d), dtype=torch.float32, device=Qs.device) if O_part is None else O_part
+    lse = torch.empty((B, Hq, Lq), dtype=torch.float32, device=Qs.device) if lse is None else lse
+    need = int(load().fedrag_partial_attn_workspace_bytes(ctypes.byref(shape), Lq, L))
+    if workspace is None and need > 0:
+        workspace = torch.empty(need, dtype=torch.uint8, device=Qs.device)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    st = load().fedrag_partial_attn_varlen(ctypes.byref(shape), Lq, L, _ptr(Qs), _ptr(Ks) if L > 0 else None,
+                                           _ptr(Vs) if L > 0 else None, _ptr(kv_lens), ctypes.c_float(softmax_scale),
+                                           _ptr(O_part), _ptr(lse), _ptr(workspace), ws_bytes, _stream())
+    _check(st, "fedrag_partial_attn_varlen")
     return O_part, lse
 
 

@@ -15,7 +15,8 @@ template <int D>
 __global__ __launch_bounds__(256) void attn_f32_kernel(const float* __restrict__ Q, const float* __restrict__ K,
                                                        const float* __restrict__ V, int Hq, int Hkv, int64_t Lq,
                                                        int64_t Lkv, int causal, int64_t total_rows, float scale,
-                                                       float* __restrict__ O, float* __restrict__ lse) {
+                                                       float* __restrict__ O, float* __restrict__ lse,
+                                                       const int32_t* __restrict__ kv_lens) {
     constexpr int CPL = D / kWave;  // output columns per lane
     __shared__ float qs[4][D];
     const int wave = threadIdx.x / kWave;
@@ -30,7 +31,12 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const float* __restrict__
     const float* Kg = K + ((int64_t)b * Hkv + g) * Lkv * D;
     const float* Vg = V + ((int64_t)b * Hkv + g) * Lkv * D;
     // keys this row sees: all of them, or (causal) those up to its own position among the last Lq tokens
-    const int64_t L = causal ? (row % Lq) + (Lkv - Lq) + 1 : Lkv;
+    int64_t L = causal ? (row % Lq) + (Lkv - Lq) + 1 : Lkv;
+    if (kv_lens) {  // padded batch of unequal sequences: only the first kv_lens[b] keys exist
+        const int64_t v = kv_lens[b];
+        const int64_t cap = v < 0 ? 0 : (v < Lkv ? v : Lkv);
+        if (L > cap) L = cap;
+    }
     for (int c = lane; c < D; c += kWave) qs[wave][c] = q[c];
     wave_lds_fence();
 
@@ -137,7 +143,7 @@ static hipError_t launch_attn_f32(const AttnProblem& p, hipStream_t stream) {
     const int64_t rows = (int64_t)p.B * p.Hq * p.Lq;
     hipLaunchKernelGGL(attn_f32_kernel<D>, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, stream, (const float*)p.Q,
                        (const float*)p.K, (const float*)p.V, p.Hq, p.Hkv, p.Lq, p.Lkv, p.causal ? 1 : 0, rows, p.scale,
-                       p.O, p.lse);
+                       p.O, p.lse, p.kv_lens);
     return hipGetLastError();
 }
 

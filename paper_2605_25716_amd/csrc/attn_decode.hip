@@ -56,7 +56,8 @@ __global__ __launch_bounds__(kDecThreads, FEDRAG_DEC_OCC) void decode_attn_kerne
                                                                      const typename T::elem* __restrict__ V, int R,
                                                                      int64_t L, int n_splits, int64_t keys_per_split,
                                                                      float scale_log2, float* __restrict__ O,
-                                                                     float* __restrict__ lse, int64_t total_rows) {
+                                                                     float* __restrict__ lse, int64_t total_rows,
+                                                                     const int32_t* __restrict__ kv_lens, int Hkv) {
     typedef typename T::elem elem;
     typedef typename T::vec8 vec8;
     typedef DecTile<T, D> Tile;
@@ -80,8 +81,16 @@ __global__ __launch_bounds__(kDecThreads, FEDRAG_DEC_OCC) void decode_attn_kerne
     const int64_t unit = blockIdx.x / n_splits;
     const int split = blockIdx.x % n_splits;
     const int64_t k_begin = (int64_t)split * keys_per_split;
+    // keys of this unit's sequence: all L rows, or the first kv_lens[b] of them (padded batch of unequal sequences);
+    // a split that starts past them is empty and returns O = 0, lse = -inf like an empty shard
+    int64_t L_seq = L;
+    if (kv_lens) {
+        const int64_t v = kv_lens[unit / Hkv];
+        L_seq = v < 0 ? 0 : (v < L ? v : L);
+    }
     int64_t k_end = k_begin + keys_per_split;
-    if (k_end > L) k_end = L;
+    if (k_end > L_seq) k_end = L_seq;
+    if (k_end < k_begin) k_end = k_begin;
 
     const elem* Qu = Q + unit * R * D;
     const char* Kb = (const char*)(K + unit * L * D);
@@ -292,7 +301,7 @@ static hipError_t launch_decode_t(const AttnProblem& p, hipStream_t stream) {
     }
     hipLaunchKernelGGL((decode_attn_kernel<T, D>), dim3((unsigned)(units * splits)), dim3(kDecThreads), 0, stream,
                        (const elem*)p.Q, (const elem*)p.K, (const elem*)p.V, R, p.Lkv, splits, per, scale_log2, Odst,
-                       Ldst, rows);
+                       Ldst, rows, p.kv_lens, p.Hkv);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || splits == 1) return e;
     return launch_lse_merge(Odst, Ldst, splits, rows, D, p.O, p.lse, stream);

@@ -46,7 +46,8 @@ template <class T, int D, bool CAUSAL>
 __global__ __launch_bounds__(kPreThreads, 1) void prefill_attn_kernel(const typename T::elem* __restrict__ Q,
                                                                       const typename T::elem* __restrict__ K,
                                                                       const typename T::elem* __restrict__ V, int Hq,
-                                                                      int Hkv, int64_t Lq, int64_t L, int q_tiles,
+                                                                      int Hkv, int64_t Lq, int64_t L_stride,
+                                                                      const int32_t* __restrict__ kv_lens, int q_tiles,
                                                                       int n_units, float scale_log2,
                                                                       float* __restrict__ O, float* __restrict__ lse) {
     typedef typename T::elem elem;
@@ -85,12 +86,25 @@ __global__ __launch_bounds__(kPreThreads, 1) void prefill_attn_kernel(const type
     const int lh = lane / 32;
 
     const elem* Qh = Q + ((int64_t)b * Hq + h) * Lq * D;
-    const char* Kg = (const char*)(K + ((int64_t)b * Hkv + g) * L * D);
-    const char* Vg = (const char*)(V + ((int64_t)b * Hkv + g) * L * D);
+    const char* Kg = (const char*)(K + ((int64_t)b * Hkv + g) * L_stride * D);
+    const char* Vg = (const char*)(V + ((int64_t)b * Hkv + g) * L_stride * D);
+    // keys of this sequence: all L_stride rows, or the first kv_lens[b] of them (padded batch of unequal sequences)
+    int64_t L = L_stride;
+    if (kv_lens) {
+        const int64_t v = kv_lens[b];
+        L = v < 0 ? 0 : (v < L_stride ? v : L_stride);
+    }
     float* Oh = O + ((int64_t)b * Hq + h) * Lq * D;
     float* Lh = lse + ((int64_t)b * Hq + h) * Lq;
 
     const int64_t q_row = (int64_t)qt * kPreQTile + wave * kPreQ + li;  // this lane's query row
+    if (L == 0) {  // no keys (workgroup-uniform, before any barrier): O = 0, lse = -inf
+        if (q_row < Lq) {
+            for (int c = lh * (D / 2); c < (lh + 1) * (D / 2); c += 4) *(f32x4_t*)(Oh + q_row * D + c) = zero_vec<f32x4_t>();
+            if (lh == 0) Lh[q_row] = -INFINITY;
+        }
+        return;
+    }
     const int64_t q_ld = q_row < Lq ? q_row : Lq - 1;
     vec8 qop[KS];  // Q'^T operands: column li, contraction slice 16 ks + 8 lh
 #pragma unroll
@@ -381,7 +395,7 @@ static hipError_t launch_prefill_t(const AttnProblem& p, hipStream_t stream) {
     const int per_unit = (p.Hq / p.Hkv) * q_tiles;
     const int64_t grid = (int64_t)8 * ((n_units + 7) / 8) * per_unit;
     hipLaunchKernelGGL((prefill_attn_kernel<T, D, CAUSAL>), dim3((unsigned)grid), dim3(kPreThreads), 0,
-                       stream, (const elem*)p.Q, (const elem*)p.K, (const elem*)p.V, p.Hq, p.Hkv, p.Lq, p.Lkv, q_tiles,
+                       stream, (const elem*)p.Q, (const elem*)p.K, (const elem*)p.V, p.Hq, p.Hkv, p.Lq, p.Lkv, p.kv_lens, q_tiles,
                        n_units, scale_log2, p.O, p.lse);
     return hipGetLastError();
 }

@@ -38,6 +38,7 @@ struct AttnProblem {
     int64_t Lq, Lkv;
     const void *Q, *K, *V;
     float scale;
+    const int32_t* kv_lens;  // NULL, or [B] device array: sequence b has only its first kv_lens[b] keys (<= Lkv)
     bool causal;  // the Lq queries are the last Lq of the Lkv tokens and see nothing after themselves
     float* O;     // [B,Hq,Lq,D]
     float* lse;   // [B,Hq,Lq]

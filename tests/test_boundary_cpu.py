@@ -143,6 +143,24 @@ def test_local_attn_and_unpermute_lse_validation(lib):
     assert u(ctypes.byref(s), 0, P(A), None, P(2 * A), None) == fb.OK
 
 
+def test_partial_attn_varlen_validation(lib):
+    s = shape()
+    f = lib.fedrag_partial_attn_varlen
+    ok_args = lambda: [ctypes.byref(s), 64, 256, P(A), P(2 * A), P(3 * A), P(6 * A), ctypes.c_float(0.1), P(4 * A),
+                       P(5 * A), None, 0, None]
+    for i in (0, 3, 4, 5, 6, 8, 9):
+        a = ok_args(); a[i] = None
+        assert f(*a) == fb.ERR_NULL
+    a = ok_args(); a[6] = P(6 * A + 2)        # misaligned lengths
+    assert f(*a) == fb.ERR_ALIAS
+    a = ok_args(); a[2] = -1
+    assert f(*a) == fb.ERR_SHAPE
+    a = ok_args(); a[1] = 1; a[2] = 1 << 20   # split path needs the workspace
+    assert f(*a) == fb.ERR_WORKSPACE
+    a = ok_args(); a[1] = 0
+    assert f(*a) == fb.OK
+
+
 def test_partial_attn_validation_and_workspace(lib):
     s = shape(B=16, Hq=32, Hkv=8)
     need = lib.fedrag_partial_attn_workspace_bytes(ctypes.byref(s), 1, 8192)

@@ -1,0 +1,43 @@
+"""GPU parity of attention over a padded batch of unequal sequences (the re-ranking workload of Section 5.2)."""
+import numpy as np
+import pytest
+import torch
+
+import parity as PT
+from paper_2605_25716_amd import binding as fb
+from paper_2605_25716_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+
+CASES = [
+    # name, B, Hq, Hkv, d, Lq, Lkv, dtype, lens
+    ("rerank_bf16", 10, 8, 8, 64, 300, 300, "bf16", [300, 257, 64, 1, 129, 0, 200, 299, 63, 128]),   # bidirectional pairs
+    ("prefill_bf16_d128", 3, 8, 2, 128, 70, 500, "bf16", [500, 33, 260]),
+    ("decode_bf16", 5, 8, 2, 128, 1, 3000, "bf16", [3000, 0, 1, 517, 2048]),                           # KV-split path
+    ("decode_f16_rows16", 2, 8, 2, 128, 4, 900, "f16", [640, 31]),
+    ("f32", 3, 4, 2, 64, 5, 100, "f32", [100, 0, 37]),
+]
+
+
+@pytest.mark.parametrize("case", CASES, ids=[c[0] for c in CASES])
+def test_partial_attn_varlen(oracle, case):
+    name, B, Hq, Hkv, d, Lq, L, dt, lens = case
+    dtype = W.torch_dtype(dt)
+    seed = 500 + len(name)
+    keys = W.make_keys(Hkv, d, Lq, L, 1, seed=seed, dtype=dtype)
+    rnd = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dtype)
+    Q = W.activations(B, Hq, Lq, d, seed=seed, tensor_id=W.TID_Q, outliers=(dt != "f32"), dtype=dtype)
+    K = W.activations(B, Hkv, L, d, seed=seed, tensor_id=W.TID_K, outliers=(dt != "f32"), dtype=dtype)
+    V = W.activations(B, Hkv, L, d, seed=seed, tensor_id=W.TID_V, outliers=(dt != "f32"), dtype=dtype)
+    Qs, Ks, Vs = rnd(oracle.scramble(Q, keys.phi_q, None)), rnd(oracle.scramble(K, keys.phi_k, None)), \
+        rnd(oracle.scramble(V, keys.phi_v, None))
+    lens_t = torch.tensor(lens, dtype=torch.int32)
+    # poison the padding: it must not reach the result
+    for b, n in enumerate(lens):
+        Ks[b, :, n:] = 3.0e4 if dt != "bf16" else 1.0e30
+        Vs[b, :, n:] = -3.0e4 if dt != "bf16" else -1.0e30
+    O, lse = fb.fedrag_partial_attn_varlen(Qs.to(DEV), Ks.to(DEV), Vs.to(DEV), lens_t.to(DEV))
+    torch.cuda.synchronize()
+    Or, lr = oracle.partial_attn_varlen(Qs, Ks, Vs, lens_t)
+    PT.check_attn(O, lse, Or, lr, dtype, name)
