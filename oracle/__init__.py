@@ -240,6 +240,32 @@ def structured(X, key, perm=None, scatter=False):
     return out
 
 
+def quantize_rows(X, bits):
+    """Section 7.5 transport codec, per row (token) of d channels: returns (codes uint8 [..., d*bits/8], params fp32
+    [..., 2] = (scale, lo)).  X: any float array/tensor [..., d]; it is taken in fp32 (exact for 16-bit storage)."""
+    if hasattr(X, "detach"):
+        X = X.detach().cpu().float().numpy()
+    X = np.ascontiguousarray(X, dtype=np.float32)
+    d = X.shape[-1]
+    assert bits in (8, 4) and d % 2 == 0
+    n = X.size // d
+    codes = np.empty(X.shape[:-1] + (d * bits // 8,), np.uint8)
+    params = np.empty(X.shape[:-1] + (2,), np.float32)
+    _load().oracle_quantize_rows(_p(X), _c_i64(n), _c_int(d), _c_int(bits), _p(codes), _p(params))
+    return codes, params
+
+
+def dequantize_rows(codes, params, bits):
+    """Inverse map of quantize_rows: fp32 values code * scale + lo (one fused multiply-add each)."""
+    codes = np.ascontiguousarray(codes, dtype=np.uint8)
+    params = np.ascontiguousarray(params, dtype=np.float32)
+    d = codes.shape[-1] * 8 // bits
+    n = codes.size // codes.shape[-1]
+    X = np.empty(codes.shape[:-1] + (d,), np.float32)
+    _load().oracle_dequantize_rows(_p(codes), _p(params), _c_i64(n), _c_int(d), _c_int(bits), _p(X))
+    return X
+
+
 def invert_perm(perm):
     perm = _i32(perm)
     inv = np.empty_like(perm)

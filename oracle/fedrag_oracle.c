@@ -14,6 +14,11 @@
  *     perm     [n_perm, L] int32    gather indices, out row j <- in row perm[j]
  * Query head h reads KV head h / (Hq / Hkv).
  *
+ * One exception to fp64: the transport codec (oracle_quantize_rows /
+ * oracle_dequantize_rows) decides integer codes by floating point, and takes
+ * those decisions in IEEE single precision, operation by operation, as its
+ * header states - the precision is part of that definition.
+ *
  * Every loop below follows the order of the equation it cites; there is no
  * blocking, fusion or reordering.  OpenMP is used only across independent
  * (batch, head) units so that the benchmark can time it on all host cores.
@@ -448,6 +453,71 @@ void oracle_structured(const double *X, const double *a, const int32_t *g1, cons
                 for (int j = 0; j < d; ++j) Yh[dst * d + j] = w[g2[ko + j]] * b[ko + j];
             }
             free(v);
+        }
+    }
+}
+
+/* ------------------------------------------------------------------------ */
+/* Transport codec (Section 7.5: "standard affine min-max quantization" of   */
+/* the intermediate states before they are sent).  One row = one token's d   */
+/* channels, quantised on its own range to `bits` bits (8 or 4):             */
+/*   lo = min_c x_c, hi = max_c x_c, levels = 2^bits - 1,                    */
+/*   scale = (hi - lo) / levels,                                             */
+/*   code_c = clamp(floor((x_c - lo) / scale + 1/2), 0, levels)   (0 when    */
+/*            scale = 0: a constant row),                                    */
+/*   dequantised value = code_c * scale + lo.                                */
+/* A code is an integer decided by floating point, so the precision of that  */
+/* decision is part of the definition: every operation above is an IEEE      */
+/* single-precision operation, rounded once (the product-sum of the          */
+/* dequantisation is one fused multiply-add).  This is the one place where   */
+/* the oracle computes in fp32 instead of fp64, on purpose.                  */
+/* params[r] = (scale, lo).  4-bit codes are packed two per byte, channel    */
+/* 2k in the low half and channel 2k+1 in the high half.                     */
+/* ------------------------------------------------------------------------ */
+void oracle_quantize_rows(const float *X, int64_t n_rows, int d, int bits, uint8_t *codes, float *params)
+{
+    const int levels = (1 << bits) - 1;
+    const int row_bytes = d * bits / 8;
+#pragma omp parallel for schedule(static) num_threads(NTHREADS())
+    for (int64_t r = 0; r < n_rows; ++r) {
+        const float *x = X + r * d;
+        float lo = x[0], hi = x[0];
+        for (int c = 1; c < d; ++c) {
+            if (x[c] < lo) lo = x[c];
+            if (x[c] > hi) hi = x[c];
+        }
+        const float range = hi - lo;
+        const float scale = range / (float)levels;
+        params[2 * r] = scale;
+        params[2 * r + 1] = lo;
+        uint8_t *out = codes + r * row_bytes;
+        for (int c = 0; c < row_bytes; ++c) out[c] = 0;
+        for (int c = 0; c < d; ++c) {
+            int q = 0;
+            if (scale > 0.0f) {
+                const float t = x[c] - lo;
+                const float u = t / scale;
+                const float v = u + 0.5f;
+                q = (int)floorf(v);
+                if (q < 0) q = 0;
+                if (q > levels) q = levels;
+            }
+            if (bits == 8) out[c] = (uint8_t)q;
+            else out[c / 2] |= (uint8_t)(q << (4 * (c % 2)));
+        }
+    }
+}
+
+void oracle_dequantize_rows(const uint8_t *codes, const float *params, int64_t n_rows, int d, int bits, float *X)
+{
+    const int row_bytes = d * bits / 8;
+#pragma omp parallel for schedule(static) num_threads(NTHREADS())
+    for (int64_t r = 0; r < n_rows; ++r) {
+        const uint8_t *in = codes + r * row_bytes;
+        const float scale = params[2 * r], lo = params[2 * r + 1];
+        for (int c = 0; c < d; ++c) {
+            const int q = bits == 8 ? in[c] : (in[c / 2] >> (4 * (c % 2))) & 15;
+            X[r * d + c] = fmaf((float)q, scale, lo);
         }
     }
 }
