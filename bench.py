@@ -227,6 +227,33 @@ def rerank_leg(torch, W, fb, dev, steps, warmup):
             "value": round(flop / (t["avg_us"] * 1e-6) / 1e12, 1), "unit": "TFLOP/s"}
 
 
+def codec_leg(torch, fb, g, steps, warmup):
+    """Transport codec on one shard's K' ([16, 8, 8192, 128] bf16): quantise to 8 bits and back, bytes = read + write."""
+    X = g["Ks"][0]
+    n = X.numel() // X.shape[-1]
+    d = X.shape[-1]
+    out = {}
+    for bits in (8, 4):
+        codes, params = fb.fedrag_quantize_rows(X, bits)
+        Xh = torch.empty_like(X)
+        q = lambda: fb.fedrag_quantize_rows(X, bits, codes=codes, params=params)
+        dq = lambda: fb.fedrag_dequantize_rows(codes, params, bits, X.dtype, X_out=Xh)
+        for _ in range(warmup):
+            q(); dq()
+        torch.cuda.synchronize()
+        timer = CallTimer(torch)
+        for _ in range(steps):
+            timer.run("q", q)
+            timer.run("dq", dq)
+        torch.cuda.synchronize()
+        t = timer.summary()
+        nbytes = n * (d * 2 + d * bits // 8 + 8)
+        out[f"{bits}bit"] = {"quantize_us": round(t["q"]["avg_us"], 2), "dequantize_us": round(t["dq"]["avg_us"], 2),
+                             "bytes": nbytes, "quantize_GB/s": round(nbytes / t["q"]["avg_us"] / 1e3, 1),
+                             "dequantize_GB/s": round(nbytes / t["dq"]["avg_us"] / 1e3, 1)}
+    return out
+
+
 def prefill_leg(torch, W, fb, dev, steps, warmup):
     """RAG prefill: partial_attn alone, 2048 queries x 16384 keys, 32/8 heads, d 128, bf16."""
     cfg = W.CONFIGS["rag_prefill"]
@@ -370,6 +397,7 @@ def main():
                                     "synchronisations (outputs checked equal to the eager ones bit for bit); "
                                     "'eager' = the same K steps launched call by call from Python")
     line["frac_hbm"] = round(line["value"] / HBM_PEAK_GBS, 4)
+    line["codec"] = codec_leg(torch, fb, g, args.steps, args.warmup)
     line["structured"] = structured_leg(torch, W, fb, g, dev, args.steps, args.warmup)
     if not args.no_prefill:
         line["rerank"] = rerank_leg(torch, W, fb, dev, max(5, args.steps // 2), args.warmup)

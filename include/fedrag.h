@@ -202,6 +202,22 @@ fedrag_status fedrag_unscramble_structured(const fedrag_shape* shape, int64_t L_
                                            const fedrag_structured_key* key_v_inv, const int32_t* perm_q,
                                            float* O_out, void* stream);
 
+/*
+ * Transport codec (Section 7.5: affine min-max quantisation of the states sent between nodes), per token row.
+ * X : n_rows rows of d values of storage type `dtype` (any [.., d] tensor of the path, e.g. K', V', Q').
+ * Per row: lo = min, hi = max, levels = 2^bits - 1, scale = (hi - lo) / levels, steps = levels / (hi - lo),
+ *     code = clamp(floor(fma(x - lo, steps, 1/2)), 0, levels)  (all 0 for a constant row);
+ *     dequantised value = fma(code, scale, lo), narrowed once (RNE) to `dtype`.
+ * All of it in IEEE single precision, operation by operation: codes and params are bit-exact functions of X.
+ * codes  : uint8 [n_rows, d * bits / 8]; 4-bit codes two per byte, channel 2k in the low half.
+ * params : fp32  [n_rows, 2] = (scale, lo), 8-byte aligned.
+ * d in {64, 128}; bits in {8, 4} (else FEDRAG_ERR_UNSUPPORTED).  Out of place; X must be finite.
+ */
+fedrag_status fedrag_quantize_rows(int64_t n_rows, int32_t d, fedrag_dtype dtype, int32_t bits,
+                                   const void* X, uint8_t* codes, float* params, void* stream);
+fedrag_status fedrag_dequantize_rows(int64_t n_rows, int32_t d, fedrag_dtype dtype, int32_t bits,
+                                     const uint8_t* codes, const float* params, void* X_out, void* stream);
+
 /* inv_out[perm[j]] = j for j in [0, L): the gather array that undoes `perm`.  Device pointers. */
 fedrag_status fedrag_invert_perm(const int32_t* perm, int64_t L, int32_t* inv_out, void* stream);
 

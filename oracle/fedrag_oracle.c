@@ -462,15 +462,15 @@ void oracle_structured(const double *X, const double *a, const int32_t *g1, cons
 /* the intermediate states before they are sent).  One row = one token's d   */
 /* channels, quantised on its own range to `bits` bits (8 or 4):             */
 /*   lo = min_c x_c, hi = max_c x_c, levels = 2^bits - 1,                    */
-/*   scale = (hi - lo) / levels,                                             */
-/*   code_c = clamp(floor((x_c - lo) / scale + 1/2), 0, levels)   (0 when    */
-/*            scale = 0: a constant row),                                    */
+/*   scale = (hi - lo) / levels,  steps = levels / (hi - lo),                */
+/*   code_c = clamp(floor((x_c - lo) * steps + 1/2), 0, levels)   (0 when    */
+/*            hi = lo: a constant row),                                      */
 /*   dequantised value = code_c * scale + lo.                                */
 /* A code is an integer decided by floating point, so the precision of that  */
 /* decision is part of the definition: every operation above is an IEEE      */
-/* single-precision operation, rounded once (the product-sum of the          */
-/* dequantisation is one fused multiply-add).  This is the one place where   */
-/* the oracle computes in fp32 instead of fp64, on purpose.                  */
+/* single-precision operation, rounded once; "(x - lo) * steps + 1/2" and    */
+/* "code * scale + lo" are one fused multiply-add each.  This is the one     */
+/* place where the oracle computes in fp32 instead of fp64, on purpose.      */
 /* params[r] = (scale, lo).  4-bit codes are packed two per byte, channel    */
 /* 2k in the low half and channel 2k+1 in the high half.                     */
 /* ------------------------------------------------------------------------ */
@@ -488,19 +488,17 @@ void oracle_quantize_rows(const float *X, int64_t n_rows, int d, int bits, uint8
         }
         const float range = hi - lo;
         const float scale = range / (float)levels;
+        const float steps = (float)levels / range;   /* unused (inf) for a constant row */
         params[2 * r] = scale;
         params[2 * r + 1] = lo;
         uint8_t *out = codes + r * row_bytes;
         for (int c = 0; c < row_bytes; ++c) out[c] = 0;
         for (int c = 0; c < d; ++c) {
             int q = 0;
-            if (scale > 0.0f) {
+            if (range > 0.0f) {
                 const float t = x[c] - lo;
-                const float u = t / scale;
-                const float v = u + 0.5f;
-                q = (int)floorf(v);
-                if (q < 0) q = 0;
-                if (q > levels) q = levels;
+                const float v = floorf(fmaf(t, steps, 0.5f));
+                q = (int)fminf(fmaxf(v, 0.0f), (float)levels);   /* clamped as a float: steps may be huge */
             }
             if (bits == 8) out[c] = (uint8_t)q;
             else out[c / 2] |= (uint8_t)(q << (4 * (c % 2)));

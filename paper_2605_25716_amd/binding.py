@@ -21,7 +21,8 @@ _DTYPES = {torch.float32: F32, torch.bfloat16: BF16, torch.float16: F16}
 EXPORTS = ("fedrag_scramble_kv", "fedrag_scramble_q", "fedrag_partial_attn",
            "fedrag_partial_attn_workspace_bytes", "fedrag_lse_merge", "fedrag_unscramble",
            "fedrag_scramble_kv_structured", "fedrag_scramble_q_structured", "fedrag_unscramble_structured",
-           "fedrag_local_attn", "fedrag_unpermute_lse", "fedrag_partial_attn_varlen", "fedrag_invert_perm", "fedrag_status_string", "fedrag_version")
+           "fedrag_local_attn", "fedrag_unpermute_lse", "fedrag_partial_attn_varlen", "fedrag_quantize_rows",
+           "fedrag_dequantize_rows", "fedrag_invert_perm", "fedrag_status_string", "fedrag_version")
 
 
 class Shape(ctypes.Structure):
@@ -76,6 +77,8 @@ def load() -> ctypes.CDLL:
         lib.fedrag_scramble_kv_structured.argtypes = [sp, i64, vp, vp, kp, kp, vp, i32, vp, vp, vp]
         lib.fedrag_scramble_q_structured.argtypes = [sp, i64, vp, kp, vp, vp, vp]
         lib.fedrag_unscramble_structured.argtypes = [sp, i64, f32p, kp, vp, f32p, vp]
+        lib.fedrag_quantize_rows.argtypes = [i64, i32, ctypes.c_int, i32, vp, vp, vp, vp]
+        lib.fedrag_dequantize_rows.argtypes = [i64, i32, ctypes.c_int, i32, vp, vp, vp, vp]
         lib.fedrag_invert_perm.argtypes = [vp, i64, vp, vp]
         lib.fedrag_status_string.argtypes = [ctypes.c_int]
         lib.fedrag_status_string.restype = ctypes.c_char_p
@@ -83,7 +86,8 @@ def load() -> ctypes.CDLL:
         for name in ("fedrag_scramble_kv", "fedrag_scramble_q", "fedrag_partial_attn", "fedrag_lse_merge",
                      "fedrag_unscramble", "fedrag_invert_perm", "fedrag_scramble_kv_structured",
                      "fedrag_scramble_q_structured", "fedrag_unscramble_structured", "fedrag_local_attn",
-                     "fedrag_unpermute_lse", "fedrag_partial_attn_varlen"):
+                     "fedrag_unpermute_lse", "fedrag_partial_attn_varlen", "fedrag_quantize_rows",
+                     "fedrag_dequantize_rows"):
             getattr(lib, name).restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -309,6 +313,28 @@ def fedrag_unscramble_structured(O_scr, key_v_inv, perm_q=None, O_out=None):
                                              _ptr(O_out), _stream())
     _check(st, "fedrag_unscramble_structured")
     return O_out
+
+
+def fedrag_quantize_rows(X, bits: int, codes=None, params=None):
+    """Transport codec (Section 7.5), per row of the last dimension.  X [..., d] -> (codes uint8 [..., d*bits/8],
+    params fp32 [..., 2] = (scale, lo))."""
+    d = X.shape[-1]
+    n = X.numel() // d
+    codes = torch.empty(X.shape[:-1] + (d * bits // 8,), dtype=torch.uint8, device=X.device) if codes is None else codes
+    params = torch.empty(X.shape[:-1] + (2,), dtype=torch.float32, device=X.device) if params is None else params
+    st = load().fedrag_quantize_rows(n, d, _DTYPES[X.dtype], bits, _ptr(X), _ptr(codes), _ptr(params), _stream())
+    _check(st, "fedrag_quantize_rows")
+    return codes, params
+
+
+def fedrag_dequantize_rows(codes, params, bits: int, dtype, X_out=None):
+    """Inverse map: codes uint8 [..., d*bits/8], params fp32 [..., 2] -> X [..., d] of `dtype`."""
+    d = codes.shape[-1] * 8 // bits
+    n = codes.numel() // codes.shape[-1]
+    X_out = torch.empty(codes.shape[:-1] + (d,), dtype=dtype, device=codes.device) if X_out is None else X_out
+    st = load().fedrag_dequantize_rows(n, d, _DTYPES[dtype], bits, _ptr(codes), _ptr(params), _ptr(X_out), _stream())
+    _check(st, "fedrag_dequantize_rows")
+    return X_out
 
 
 def fedrag_invert_perm(perm, inv_out=None):

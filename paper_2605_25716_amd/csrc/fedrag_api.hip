@@ -381,6 +381,39 @@ fedrag_status fedrag_unscramble_structured(const fedrag_shape* shape, int64_t L_
     return dev(launch_rows_transform(j, (hipStream_t)stream));
 }
 
+static fedrag_status codec_call(bool quantize, int64_t n_rows, int32_t d, fedrag_dtype dtype, int32_t bits,
+                                const void* X, const void* codes, const void* params, void* stream) {
+    if (n_rows < 0 || n_rows > INT64_MAX / 1024) return FEDRAG_ERR_SHAPE;
+    if (d != 64 && d != 128) return FEDRAG_ERR_UNSUPPORTED;
+    if (bits != 8 && bits != 4) return FEDRAG_ERR_UNSUPPORTED;
+    if (dtype != FEDRAG_F32 && dtype != FEDRAG_BF16 && dtype != FEDRAG_F16) return FEDRAG_ERR_UNSUPPORTED;
+    if (!X || !codes || !params) return FEDRAG_ERR_NULL;
+    if (!aligned16(X) || !aligned16(codes) || (reinterpret_cast<uintptr_t>(params) & 7u)) return FEDRAG_ERR_ALIAS;
+    const size_t xb = (size_t)n_rows * d * elem_size(dtype), cb = (size_t)n_rows * d * bits / 8, pb = (size_t)n_rows * 8;
+    if (overlaps(X, xb, codes, cb) || overlaps(X, xb, params, pb) || overlaps(codes, cb, params, pb))
+        return FEDRAG_ERR_ALIAS;
+    CodecJob j{};
+    j.quantize = quantize;
+    j.n_rows = n_rows;
+    j.D = d;
+    j.dtype = dtype;
+    j.bits = bits;
+    j.X = const_cast<void*>(X);
+    j.codes = (uint8_t*)const_cast<void*>(codes);
+    j.params = (float*)const_cast<void*>(params);
+    return dev(launch_codec(j, (hipStream_t)stream));
+}
+
+fedrag_status fedrag_quantize_rows(int64_t n_rows, int32_t d, fedrag_dtype dtype, int32_t bits, const void* X,
+                                   uint8_t* codes, float* params, void* stream) {
+    return codec_call(true, n_rows, d, dtype, bits, X, codes, params, stream);
+}
+
+fedrag_status fedrag_dequantize_rows(int64_t n_rows, int32_t d, fedrag_dtype dtype, int32_t bits,
+                                     const uint8_t* codes, const float* params, void* X_out, void* stream) {
+    return codec_call(false, n_rows, d, dtype, bits, X_out, codes, params, stream);
+}
+
 fedrag_status fedrag_invert_perm(const int32_t* perm, int64_t L, int32_t* inv_out, void* stream) {
     if (L < 0 || L > INT32_MAX) return FEDRAG_ERR_SHAPE;
     if (!perm || !inv_out) return FEDRAG_ERR_NULL;

@@ -68,4 +68,17 @@ hipError_t launch_fill_empty(float* O, float* lse, int64_t rows, int D, hipStrea
 hipError_t launch_scatter_rows_f32(const float* in, const int32_t* perm, int64_t n_bh, int64_t L, float* out,
                                    hipStream_t stream);
 
+// Transport codec job: quantize (X -> codes, params) or dequantize (codes, params -> X); X has n_rows rows of D values.
+struct CodecJob {
+    bool quantize;
+    int64_t n_rows;
+    int D;       // 64 or 128
+    int dtype;   // fedrag_dtype of X
+    int bits;    // 8 or 4
+    void* X;
+    uint8_t* codes;   // [n_rows, D * bits / 8]
+    float* params;    // [n_rows, 2] = (scale, lo)
+};
+hipError_t launch_codec(const CodecJob& job, hipStream_t stream);
+
 }  // namespace fedrag

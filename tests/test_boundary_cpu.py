@@ -161,6 +161,28 @@ def test_partial_attn_varlen_validation(lib):
     assert f(*a) == fb.OK
 
 
+def test_codec_validation(lib):
+    for f in (lib.fedrag_quantize_rows, lib.fedrag_dequantize_rows):
+        ok = lambda: [100, 128, fb.BF16, 8, P(A), P(4 * A), P(8 * A), None]
+        for i in (4, 5, 6):
+            a = ok(); a[i] = None
+            assert f(*a) == fb.ERR_NULL
+        a = ok(); a[0] = -1
+        assert f(*a) == fb.ERR_SHAPE
+        a = ok(); a[1] = 96
+        assert f(*a) == fb.ERR_UNSUPPORTED
+        a = ok(); a[3] = 5
+        assert f(*a) == fb.ERR_UNSUPPORTED
+        a = ok(); a[2] = 9
+        assert f(*a) == fb.ERR_UNSUPPORTED
+        a = ok(); a[6] = P(8 * A + 4)          # params need 8-byte alignment
+        assert f(*a) == fb.ERR_ALIAS
+        a = ok(); a[5] = P(A + 256)            # codes inside X
+        assert f(*a) == fb.ERR_ALIAS
+        a = ok(); a[0] = 0
+        assert f(*a) == fb.OK
+
+
 def test_partial_attn_validation_and_workspace(lib):
     s = shape(B=16, Hq=32, Hkv=8)
     need = lib.fedrag_partial_attn_workspace_bytes(ctypes.byref(s), 1, 8192)

@@ -1,0 +1,90 @@
+"""GPU parity of the transport codec (Section 7.5) - bit-exact codes, parameters and dequantised values - and its
+effect on the attention result: the variant of the structured scramble without S2 under 8-bit transport."""
+import numpy as np
+import pytest
+import torch
+
+import parity as PT
+from paper_2605_25716_amd import binding as fb
+from paper_2605_25716_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+
+
+def data(seed, shape, dtype):
+    r = np.random.default_rng(seed)
+    x = r.standard_normal(shape) * np.exp(r.uniform(-4, 4, size=shape[:-1] + (1,))) + r.uniform(-3, 3, size=shape[:-1] + (1,))
+    x[..., 0, :] = 0.75                    # a constant row
+    return torch.from_numpy(x).to(dtype)
+
+
+@pytest.mark.parametrize("bits", [8, 4])
+@pytest.mark.parametrize("dt,d,shape", [("bf16", 128, (2, 3, 1001)), ("bf16", 64, (1, 2, 77)), ("f16", 128, (5, 333)),
+                                        ("f32", 64, (3, 130)), ("f32", 128, (1,))])
+def test_codec_bit_exact(oracle, bits, dt, d, shape):
+    dtype = W.torch_dtype(dt)
+    X = data(bits + d + len(shape), shape + (d,), dtype)
+    codes, params = fb.fedrag_quantize_rows(X.to(DEV), bits)
+    Xh = fb.fedrag_dequantize_rows(codes, params, bits, dtype)
+    torch.cuda.synchronize()
+    c_ref, p_ref = oracle.quantize_rows(X, bits)
+    assert np.array_equal(codes.cpu().numpy(), c_ref), "codes differ"
+    assert np.array_equal(params.cpu().numpy().view(np.uint32), p_ref.view(np.uint32)), "scale / lo differ"
+    x_ref = torch.from_numpy(oracle.dequantize_rows(c_ref, p_ref, bits)).to(dtype)      # one RNE narrowing
+    assert torch.equal(Xh.cpu(), x_ref), "dequantised values differ"
+
+
+def test_codec_at_shard_size_sampled(oracle):
+    cfg = W.CONFIGS["llama8b_decode"]
+    dt = W.torch_dtype(cfg.dtype)
+    K = W.activations(cfg.batch, cfg.n_kv_heads, cfg.L_kv, cfg.d_head, seed=cfg.seed, tensor_id=W.TID_K, outliers=True,
+                      dtype=dt, device=DEV)
+    for bits in (8, 4):
+        codes, params = fb.fedrag_quantize_rows(K, bits)
+        Kh = fb.fedrag_dequantize_rows(codes, params, bits, dt)
+        torch.cuda.synchronize()
+        rng = np.random.default_rng(bits)
+        for _ in range(3):
+            b, g = int(rng.integers(cfg.batch)), int(rng.integers(cfg.n_kv_heads))
+            c_ref, p_ref = oracle.quantize_rows(K[b, g].cpu(), bits)
+            assert np.array_equal(codes[b, g].cpu().numpy(), c_ref)
+            assert np.array_equal(params[b, g].cpu().numpy().view(np.uint32), p_ref.view(np.uint32))
+            assert torch.equal(Kh[b, g].cpu(), torch.from_numpy(oracle.dequantize_rows(c_ref, p_ref, bits)).to(dt))
+        # property over the whole tensor: within half a step, plus the storage rounding (2^-9 relative, bf16) of the
+        # reconstruction, whose magnitude is at most |x| + step / 2
+        step = params[..., :1]
+        err = (Kh.float() - K.float()).abs()
+        assert bool((err <= 0.5 * step * (1 + 2.0 ** -7) + 2.0 ** -8 * K.float().abs() + 1e-30).all())
+
+
+def test_eight_bit_transport_with_and_without_s2(oracle):
+    """Section 7.5: with both scalings the scrambled states have a wide per-token range and 8-bit transport hurts;
+    leaving S2 out repairs it.  Synthetic N(0,1) activations, structured keys, K' and V' sent through the codec."""
+    B, Hq, Hkv, d, Lq, L = 1, 8, 2, 128, 64, 1024
+    dt = torch.bfloat16
+    seed = 606
+    Q = W.activations(B, Hq, Lq, d, seed=seed, tensor_id=W.TID_Q, outliers=False, dtype=dt)
+    K = W.activations(B, Hkv, L, d, seed=seed, tensor_id=W.TID_K, outliers=False, dtype=dt)
+    V = W.activations(B, Hkv, L, d, seed=seed, tensor_id=W.TID_V, outliers=False, dtype=dt)
+    ref, _ = oracle.plain_attention(Q, K, V)
+    errs = {}
+    for use_s2 in (True, False):
+        ks = W.make_structured_keys(Hkv, d, Lq, L, 1, seed=seed, dtype=dt, use_s2=use_s2)
+        dk = lambda key: tuple(t.to(DEV) for t in key)
+        pq = ks.perm_q.to(DEV)
+        Qs = fb.fedrag_scramble_q_structured(Q.to(DEV), dk(ks.q), pq)
+        Ks, Vs = fb.fedrag_scramble_kv_structured(K.to(DEV), V.to(DEV), dk(ks.k), dk(ks.v), ks.perm_kv[0].to(DEV))
+        for bits in (16, 8):
+            if bits == 16:
+                Kt, Vt = Ks, Vs
+            else:
+                Kt = fb.fedrag_dequantize_rows(*fb.fedrag_quantize_rows(Ks, 8), 8, dt)
+                Vt = fb.fedrag_dequantize_rows(*fb.fedrag_quantize_rows(Vs, 8), 8, dt)
+            O, _ = fb.fedrag_partial_attn(Qs, Kt, Vt)
+            out = fb.fedrag_unscramble_structured(O, dk(ks.v_inv), pq)
+            errs[(use_s2, bits)] = float(np.linalg.norm(PT.f64(out) - ref) / np.linalg.norm(ref))
+    print("relative attention-output error (Frobenius): " +
+          ", ".join(f"S2={'on' if k[0] else 'off'} {k[1]}-bit {100 * v:.2f} %" for k, v in errs.items()))
+    assert errs[(False, 8)] < errs[(True, 8)]
+    assert errs[(False, 8)] < 0.10 and errs[(True, 8)] > 0.25
