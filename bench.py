@@ -251,6 +251,22 @@ def codec_leg(torch, fb, g, steps, warmup):
         out[f"{bits}bit"] = {"quantize_us": round(t["q"]["avg_us"], 2), "dequantize_us": round(t["dq"]["avg_us"], 2),
                              "bytes": nbytes, "quantize_GB/s": round(nbytes / t["q"]["avg_us"] / 1e3, 1),
                              "dequantize_GB/s": round(nbytes / t["dq"]["avg_us"] / 1e3, 1)}
+    # Enc with the codec as its epilogue (what a Context Owner sends): one shard, K and V
+    cfg = g["cfg"]
+    outs = fb.fedrag_scramble_kv_quantized(g["K"][0], g["V"][0], g["phi_k"], g["phi_v"], g["perm_kv"][0], 8,
+                                           n_q_heads=cfg.n_q_heads)
+    call = lambda: fb.fedrag_scramble_kv_quantized(g["K"][0], g["V"][0], g["phi_k"], g["phi_v"], g["perm_kv"][0], 8,
+                                                   n_q_heads=cfg.n_q_heads, out=outs)
+    for _ in range(warmup):
+        call()
+    torch.cuda.synchronize()
+    timer = CallTimer(torch)
+    for _ in range(steps):
+        timer.run("f", call)
+    torch.cuda.synchronize()
+    us = timer.summary()["f"]["avg_us"]
+    nb = 2 * n * (d * 2 + d + 8) + 4 * cfg.L_kv
+    out["scramble_kv_quantized_8bit"] = {"avg_us": round(us, 2), "bytes": nb, "GB/s": round(nb / us / 1e3, 1)}
     return out
 
 

@@ -218,6 +218,28 @@ fedrag_status fedrag_quantize_rows(int64_t n_rows, int32_t d, fedrag_dtype dtype
 fedrag_status fedrag_dequantize_rows(int64_t n_rows, int32_t d, fedrag_dtype dtype, int32_t bits,
                                      const uint8_t* codes, const float* params, void* X_out, void* stream);
 
+/*
+ * fedrag_scramble_kv / fedrag_scramble_kv_structured with the transport codec as the epilogue (Section 7.5: the
+ * scrambled K', V' are what travels to the Compute Node): each row of K', V' is narrowed to the storage type as
+ * usual and then quantised exactly as fedrag_quantize_rows would quantise it, so the outputs equal
+ * fedrag_quantize_rows(fedrag_scramble_kv(...)) bit for bit while K', V' are never written in 16 bits.
+ * K_codes, V_codes : uint8 [B,Hkv,L,d*bits/8];  K_params, V_params : fp32 [B,Hkv,L,2].  16-bit storage only
+ * (FEDRAG_F32: FEDRAG_ERR_UNSUPPORTED); bits in {8, 4}.  Other arguments and errors as the unquantised calls.
+ */
+fedrag_status fedrag_scramble_kv_quantized(const fedrag_shape* shape, int64_t L_kv,
+                                           const void* K, const void* V,
+                                           const void* phi_k, const void* phi_v,
+                                           const int32_t* perm_kv, int32_t n_perm, int32_t bits,
+                                           uint8_t* K_codes, float* K_params,
+                                           uint8_t* V_codes, float* V_params, void* stream);
+fedrag_status fedrag_scramble_kv_structured_quantized(const fedrag_shape* shape, int64_t L_kv,
+                                                      const void* K, const void* V,
+                                                      const fedrag_structured_key* key_k,
+                                                      const fedrag_structured_key* key_v,
+                                                      const int32_t* perm_kv, int32_t n_perm, int32_t bits,
+                                                      uint8_t* K_codes, float* K_params,
+                                                      uint8_t* V_codes, float* V_params, void* stream);
+
 /* inv_out[perm[j]] = j for j in [0, L): the gather array that undoes `perm`.  Device pointers. */
 fedrag_status fedrag_invert_perm(const int32_t* perm, int64_t L, int32_t* inv_out, void* stream);
 

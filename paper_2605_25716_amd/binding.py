@@ -22,7 +22,8 @@ EXPORTS = ("fedrag_scramble_kv", "fedrag_scramble_q", "fedrag_partial_attn",
            "fedrag_partial_attn_workspace_bytes", "fedrag_lse_merge", "fedrag_unscramble",
            "fedrag_scramble_kv_structured", "fedrag_scramble_q_structured", "fedrag_unscramble_structured",
            "fedrag_local_attn", "fedrag_unpermute_lse", "fedrag_partial_attn_varlen", "fedrag_quantize_rows",
-           "fedrag_dequantize_rows", "fedrag_invert_perm", "fedrag_status_string", "fedrag_version")
+           "fedrag_dequantize_rows", "fedrag_scramble_kv_quantized", "fedrag_scramble_kv_structured_quantized",
+           "fedrag_invert_perm", "fedrag_status_string", "fedrag_version")
 
 
 class Shape(ctypes.Structure):
@@ -79,6 +80,8 @@ def load() -> ctypes.CDLL:
         lib.fedrag_unscramble_structured.argtypes = [sp, i64, f32p, kp, vp, f32p, vp]
         lib.fedrag_quantize_rows.argtypes = [i64, i32, ctypes.c_int, i32, vp, vp, vp, vp]
         lib.fedrag_dequantize_rows.argtypes = [i64, i32, ctypes.c_int, i32, vp, vp, vp, vp]
+        lib.fedrag_scramble_kv_quantized.argtypes = [sp, i64, vp, vp, vp, vp, vp, i32, i32, vp, vp, vp, vp, vp]
+        lib.fedrag_scramble_kv_structured_quantized.argtypes = [sp, i64, vp, vp, kp, kp, vp, i32, i32, vp, vp, vp, vp, vp]
         lib.fedrag_invert_perm.argtypes = [vp, i64, vp, vp]
         lib.fedrag_status_string.argtypes = [ctypes.c_int]
         lib.fedrag_status_string.restype = ctypes.c_char_p
@@ -87,7 +90,8 @@ def load() -> ctypes.CDLL:
                      "fedrag_unscramble", "fedrag_invert_perm", "fedrag_scramble_kv_structured",
                      "fedrag_scramble_q_structured", "fedrag_unscramble_structured", "fedrag_local_attn",
                      "fedrag_unpermute_lse", "fedrag_partial_attn_varlen", "fedrag_quantize_rows",
-                     "fedrag_dequantize_rows"):
+                     "fedrag_dequantize_rows", "fedrag_scramble_kv_quantized",
+                     "fedrag_scramble_kv_structured_quantized"):
             getattr(lib, name).restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -335,6 +339,31 @@ def fedrag_dequantize_rows(codes, params, bits: int, dtype, X_out=None):
     st = load().fedrag_dequantize_rows(n, d, _DTYPES[dtype], bits, _ptr(codes), _ptr(params), _ptr(X_out), _stream())
     _check(st, "fedrag_dequantize_rows")
     return X_out
+
+
+def fedrag_scramble_kv_quantized(K, V, phi_k, phi_v, perm_kv, bits: int, n_q_heads: Optional[int] = None,
+                                 structured: bool = False, out=None):
+    """Enc of a KV shard with the transport codec as epilogue.  phi_k / phi_v: dense matrices, or structured keys
+    with structured=True.  Returns (K_codes, K_params, V_codes, V_params)."""
+    B, Hkv, L, d = K.shape
+    shape = make_shape(B, n_q_heads or Hkv, Hkv, d, K.dtype)
+    mk_c = lambda: torch.empty((B, Hkv, L, d * bits // 8), dtype=torch.uint8, device=K.device)
+    mk_p = lambda: torch.empty((B, Hkv, L, 2), dtype=torch.float32, device=K.device)
+    Kc, Kp, Vc, Vp = (mk_c(), mk_p(), mk_c(), mk_p()) if out is None else out
+    n_perm = 0
+    if perm_kv is not None:
+        n_perm = 1 if perm_kv.dim() == 1 else perm_kv.shape[0]
+    if structured:
+        kk, kv = _key(phi_k), _key(phi_v)
+        st = load().fedrag_scramble_kv_structured_quantized(ctypes.byref(shape), L, _ptr(K), _ptr(V), ctypes.byref(kk),
+                                                            ctypes.byref(kv), _ptr(perm_kv), n_perm, bits, _ptr(Kc),
+                                                            _ptr(Kp), _ptr(Vc), _ptr(Vp), _stream())
+    else:
+        st = load().fedrag_scramble_kv_quantized(ctypes.byref(shape), L, _ptr(K), _ptr(V), _ptr(phi_k), _ptr(phi_v),
+                                                 _ptr(perm_kv), n_perm, bits, _ptr(Kc), _ptr(Kp), _ptr(Vc), _ptr(Vp),
+                                                 _stream())
+    _check(st, "fedrag_scramble_kv_quantized")
+    return Kc, Kp, Vc, Vp
 
 
 def fedrag_invert_perm(perm, inv_out=None):

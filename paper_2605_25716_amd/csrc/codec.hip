@@ -5,7 +5,7 @@
 // Every operation is a single-precision IEEE operation (the codes are integers decided by floating point, so the
 // precision is part of the definition).  params[row] = (scale, lo); 4-bit codes are packed two per byte, channel 2k
 // in the low half.  HBM-bound streaming kernels: a row is held by D/8 lanes with 8 channels each (one 16-byte load
-// for 16-bit storage), the row's range is reduced across those lanes with shuffles, codes leave as 8 (or 4)
+// for 16-bit storage), the row's range is reduced across those lanes with data-parallel lane moves, codes leave as 8 (or 4)
 // contiguous bytes per lane.
 #include "fedrag_device.h"
 #include "fedrag_host.h"
@@ -82,20 +82,17 @@ __global__ __launch_bounds__(kCodecThreads) void quantize_rows_kernel(const char
             float lo = x[u][0], hi = x[u][0];
 #pragma unroll
             for (int e = 1; e < 8; ++e) { lo = fminf(lo, x[u][e]); hi = fmaxf(hi, x[u][e]); }
-#pragma unroll
-            for (int o = 1; o < LPR; o <<= 1) {
-                lo = fminf(lo, __shfl_xor(lo, o));
-                hi = fmaxf(hi, __shfl_xor(hi, o));
-            }
+            lo = group_min<LPR>(lo);
+            hi = group_max<LPR>(hi);
             const float range = hi - lo;
             const float scale = range / (float)LEVELS;
-            const float steps = (float)LEVELS / range;
+            // x - lo >= 0, so the sum is >= 1/2: converting to unsigned truncates = floors, and only the upper clamp
+            // can act; a constant row (range 0) gets steps 0, hence code 0
+            const float steps = range > 0.0f ? (float)LEVELS / range : 0.0f;
             uint32_t q[8];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const float v = floorf(__builtin_fmaf(x[u][e] - lo, steps, 0.5f));
-                q[e] = range > 0.0f ? (uint32_t)fminf(fmaxf(v, 0.0f), (float)LEVELS) : 0u;
-            }
+            for (int e = 0; e < 8; ++e)
+                q[e] = (uint32_t)fminf(__builtin_fmaf(x[u][e] - lo, steps, 0.5f), (float)LEVELS);
             if (row[u] < n_rows) {
                 uint8_t* out = codes + row[u] * CODE_ROWB;
                 if (BITS == 8) {

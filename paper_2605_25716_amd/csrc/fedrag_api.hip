@@ -381,6 +381,79 @@ fedrag_status fedrag_unscramble_structured(const fedrag_shape* shape, int64_t L_
     return dev(launch_rows_transform(j, (hipStream_t)stream));
 }
 
+// Enc of a KV shard with the transport codec as its epilogue; exactly one of (phi_k, phi_v) / (key_k, key_v) is given.
+static fedrag_status scramble_kv_quantized(const fedrag_shape* shape, int64_t L_kv, const void* K, const void* V,
+                                           const void* phi_k, const void* phi_v, const fedrag_structured_key* key_k,
+                                           const fedrag_structured_key* key_v, const int32_t* perm_kv, int32_t n_perm,
+                                           int32_t bits, uint8_t* K_codes, float* K_params, uint8_t* V_codes,
+                                           float* V_params, void* stream) {
+    fedrag_status st = check_shape(shape, true);
+    if (st != FEDRAG_OK) return st;
+    if (shape->dtype == FEDRAG_F32) return FEDRAG_ERR_UNSUPPORTED;  // the codec epilogue is for 16-bit storage
+    if (bits != 8 && bits != 4) return FEDRAG_ERR_UNSUPPORTED;
+    if (L_kv < 0 || L_kv > INT32_MAX) return FEDRAG_ERR_SHAPE;
+    if (!K || !V || !K_codes || !K_params || !V_codes || !V_params) return FEDRAG_ERR_NULL;
+    const bool structured = key_k != nullptr || key_v != nullptr;
+    if (structured) {
+        if ((st = check_key(key_k)) != FEDRAG_OK || (st = check_key(key_v)) != FEDRAG_OK) return st;
+    } else {
+        if (!phi_k || !phi_v) return FEDRAG_ERR_NULL;
+        if (!aligned16(phi_k) || !aligned16(phi_v)) return FEDRAG_ERR_ALIAS;
+    }
+    if (perm_kv && n_perm != 1 && n_perm != shape->batch) return FEDRAG_ERR_SHAPE;
+    int64_t n;
+    if (!tensor_elems(shape->batch, shape->n_kv_heads, L_kv, shape->d_head, &n)) return FEDRAG_ERR_SHAPE;
+    const size_t xb = (size_t)n * 2, cb = (size_t)n * bits / 8, pb = (size_t)(n / shape->d_head) * 8;
+    if (!aligned16(K) || !aligned16(V) || !aligned16(K_codes) || !aligned16(V_codes) ||
+        (reinterpret_cast<uintptr_t>(K_params) & 7u) || (reinterpret_cast<uintptr_t>(V_params) & 7u) ||
+        (reinterpret_cast<uintptr_t>(perm_kv) & 3u))
+        return FEDRAG_ERR_ALIAS;
+    const void* outs[4] = {K_codes, V_codes, K_params, V_params};
+    const size_t out_bytes[4] = {cb, cb, pb, pb};
+    for (int a = 0; a < 4; ++a) {
+        if (overlaps(outs[a], out_bytes[a], K, xb) || overlaps(outs[a], out_bytes[a], V, xb)) return FEDRAG_ERR_ALIAS;
+        for (int b = a + 1; b < 4; ++b)
+            if (overlaps(outs[a], out_bytes[a], outs[b], out_bytes[b])) return FEDRAG_ERR_ALIAS;
+    }
+    RowsJob j{};
+    j.n_jobs = 2;
+    j.X[0] = K; j.Phi[0] = phi_k; j.Y[0] = K_codes; j.params[0] = K_params;
+    j.X[1] = V; j.Phi[1] = phi_v; j.Y[1] = V_codes; j.params[1] = V_params;
+    if (structured) {
+        set_key(j, 0, key_k);
+        set_key(j, 1, key_v);
+    }
+    j.quant_bits = bits;
+    j.perm = perm_kv;
+    j.perm_batch_stride = (perm_kv && n_perm > 1) ? L_kv : 0;
+    j.BH = (int64_t)shape->batch * shape->n_kv_heads;
+    j.H = shape->n_kv_heads;
+    j.G = 1;
+    j.L = L_kv;
+    j.D = shape->d_head;
+    j.dtype = shape->dtype;
+    j.scatter = false;
+    return dev(launch_rows_transform(j, (hipStream_t)stream));
+}
+
+fedrag_status fedrag_scramble_kv_quantized(const fedrag_shape* shape, int64_t L_kv, const void* K, const void* V,
+                                           const void* phi_k, const void* phi_v, const int32_t* perm_kv, int32_t n_perm,
+                                           int32_t bits, uint8_t* K_codes, float* K_params, uint8_t* V_codes,
+                                           float* V_params, void* stream) {
+    return scramble_kv_quantized(shape, L_kv, K, V, phi_k, phi_v, nullptr, nullptr, perm_kv, n_perm, bits, K_codes,
+                                 K_params, V_codes, V_params, stream);
+}
+
+fedrag_status fedrag_scramble_kv_structured_quantized(const fedrag_shape* shape, int64_t L_kv, const void* K,
+                                                      const void* V, const fedrag_structured_key* key_k,
+                                                      const fedrag_structured_key* key_v, const int32_t* perm_kv,
+                                                      int32_t n_perm, int32_t bits, uint8_t* K_codes, float* K_params,
+                                                      uint8_t* V_codes, float* V_params, void* stream) {
+    if (!key_k || !key_v) return FEDRAG_ERR_NULL;
+    return scramble_kv_quantized(shape, L_kv, K, V, nullptr, nullptr, key_k, key_v, perm_kv, n_perm, bits, K_codes,
+                                 K_params, V_codes, V_params, stream);
+}
+
 static fedrag_status codec_call(bool quantize, int64_t n_rows, int32_t d, fedrag_dtype dtype, int32_t bits,
                                 const void* X, const void* codes, const void* params, void* stream) {
     if (n_rows < 0 || n_rows > INT64_MAX / 1024) return FEDRAG_ERR_SHAPE;

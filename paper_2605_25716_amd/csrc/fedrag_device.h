@@ -73,6 +73,31 @@ __device__ __forceinline__ float fast_log2(float x) { return __builtin_amdgcn_lo
 __device__ __forceinline__ float xor32_max(float x) { return fmaxf(x, __shfl_xor(x, 32)); }
 __device__ __forceinline__ float xor32_sum(float x) { return x + __shfl_xor(x, 32); }
 
+// min / max over aligned groups of N = 8 or 16 consecutive lanes, result in every lane of the group, with data-parallel
+// primitives only (no LDS crossbar): exchange inside quads, then mirror the half row (lane k <-> 7 - k: the other
+// quad, whose lanes already agree), then mirror the row of 16.
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float x) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xf, 0xf, true));
+}
+template <int N, class Op>
+__device__ __forceinline__ float group_reduce(float x, Op op) {
+    static_assert(N == 8 || N == 16, "groups of 8 or 16 lanes");
+    x = op(x, dpp_move<0xB1>(x));   // quad_perm [1,0,3,2]
+    x = op(x, dpp_move<0x4E>(x));   // quad_perm [2,3,0,1]
+    x = op(x, dpp_move<0x141>(x));  // row_half_mirror
+    if (N == 16) x = op(x, dpp_move<0x140>(x));  // row_mirror
+    return x;
+}
+template <int N>
+__device__ __forceinline__ float group_min(float x) {
+    return group_reduce<N>(x, [](float a, float b) { return fminf(a, b); });
+}
+template <int N>
+__device__ __forceinline__ float group_max(float x) {
+    return group_reduce<N>(x, [](float a, float b) { return fmaxf(a, b); });
+}
+
 // Keep a value's computation above this point: the compiler may otherwise sink pure register arithmetic towards
 // its first use (past a barrier, into the next loop iteration), out of the scheduling region it was written for.
 template <class V>

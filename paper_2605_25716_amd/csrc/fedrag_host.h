@@ -18,6 +18,8 @@ struct RowsJob {
     const int32_t* p_in[2];
     const int32_t* p_out[2];
     const float* s_out[2];
+    int quant_bits;           // 0, or 8 / 4: 16-bit gather form only - Y[i] receives the transport codes of the rows
+    float* params[2];         //   and params[i] their (scale, lo), [BH * L, 2]
     void* Y[2];
     const int32_t* perm;      // NULL = identity
     int64_t perm_batch_stride;  // 0 (one permutation for all sequences) or L

@@ -33,6 +33,9 @@ struct ScrambleJob {
     const int32_t* p_in;
     const int32_t* p_out;
     const float* s_out;
+    // quantised output (transport codec of Section 7.5 applied to the narrowed rows): Y holds the codes, params the
+    // per-row (scale, lo)
+    float* params;
 };
 
 // Entry (k, n) of S1 P1 Hs P2 with the permutations as gathers and Hs the +-1 Sylvester matrix:
@@ -52,7 +55,9 @@ __device__ __forceinline__ float structured_entry(float s_in_k, int p_in_inv_k, 
 // A ring of NBUF register tile sets keeps NBUF-1 gathered tiles (8 KiB each) in flight per wave behind the LDS
 // staging and the MFMAs (it runs straight through the slab boundaries); the gather indices of a tile are fetched
 // one step before its rows.  Tiles that start past the end of a slab are computed on clamped rows and not stored.
-template <class T, int D, bool ST>
+// QB = 0: rows leave in the storage type.  QB = 8 or 4: each narrowed row goes through the transport codec instead
+// (same arithmetic as quantize_rows_kernel on the stored row) and leaves as codes plus (scale, lo).
+template <class T, int D, bool ST, int QB>
 __global__ __launch_bounds__(kScrThreads, 1) void scramble_rows_kernel(ScrambleJob job0, ScrambleJob job1,
                                                                        const int32_t* __restrict__ perm,
                                                                        int64_t perm_batch_stride,  // 0 or L
@@ -207,7 +212,47 @@ __global__ __launch_bounds__(kScrThreads, 1) void scramble_rows_kernel(ScrambleJ
         for (int k = 0; k < NI; ++k) {
             const int64_t j = row0 + k * RPI + ld_row;
             const vec8 v = *(const vec8*)(&my[(k * RPI + ld_row) * LDP + ld_col]);
-            if (j < L) __builtin_nontemporal_store(v, (vec8*)(Y + j * D + ld_col));
+            if (QB == 0) {
+                if (j < L) __builtin_nontemporal_store(v, (vec8*)(Y + j * D + ld_col));
+            } else {
+                // the row is spread over CH consecutive lanes, 8 channels each
+                constexpr int LEVELS = (1 << (QB ? QB : 1)) - 1;
+                float x[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) x[e] = T::to_float(v[e]);
+                float lo = x[0], hi = x[0];
+#pragma unroll
+                for (int e = 1; e < 8; ++e) { lo = fminf(lo, x[e]); hi = fmaxf(hi, x[e]); }
+                lo = group_min<CH>(lo);
+                hi = group_max<CH>(hi);
+                const float range = hi - lo;
+                const float scale = range / (float)LEVELS;
+                // x - lo >= 0, so the sum is >= 1/2: converting to unsigned truncates = floors, and only the upper
+                // clamp can act; a constant row (range 0) gets steps 0, hence code 0
+                const float steps = range > 0.0f ? (float)LEVELS / range : 0.0f;
+                uint32_t q[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    q[e] = (uint32_t)fminf(__builtin_fmaf(x[e] - lo, steps, 0.5f), (float)LEVELS);
+                if (j < L) {
+                    const int64_t row = slab_off(i) / D + j;  // row index over the whole tensor
+                    uint8_t* out = (uint8_t*)job.Y + row * (D * QB / 8);
+                    if (QB == 8) {
+                        u32x2_t w;
+                        w[0] = q[0] | (q[1] << 8) | (q[2] << 16) | (q[3] << 24);
+                        w[1] = q[4] | (q[5] << 8) | (q[6] << 16) | (q[7] << 24);
+                        __builtin_nontemporal_store(w, (u32x2_t*)(out + (lane % CH) * 8));
+                    } else {
+                        const uint32_t w = q[0] | (q[1] << 4) | (q[2] << 8) | (q[3] << 12) | (q[4] << 16) |
+                                           (q[5] << 20) | (q[6] << 24) | (q[7] << 28);
+                        __builtin_nontemporal_store(w, (uint32_t*)(out + (lane % CH) * 4));
+                    }
+                    if (lane % CH == 0) {
+                        job.params[2 * row] = scale;
+                        job.params[2 * row + 1] = lo;
+                    }
+                }
+            }
         }
         wave_lds_fence();  // reads of the output tile done before the next tile's rows land
     };
@@ -321,7 +366,7 @@ __global__ void invert_perm_kernel(const int32_t* __restrict__ perm, int64_t L, 
 static int ceil_div_i64(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
 
 static ScrambleJob device_job(const RowsJob& j, int i) {
-    return ScrambleJob{j.X[i], j.Phi[i], j.Y[i], j.s_in[i], j.p_in[i], j.p_out[i], j.s_out[i]};
+    return ScrambleJob{j.X[i], j.Phi[i], j.Y[i], j.s_in[i], j.p_in[i], j.p_out[i], j.s_out[i], j.params[i]};
 }
 
 template <class T, int D>
@@ -340,12 +385,19 @@ static hipError_t launch_scramble16(const RowsJob& j, hipStream_t stream) {
     if (b_groups > B) b_groups = B;
     dim3 grid((unsigned)(j.H * members * b_groups), (unsigned)j.n_jobs);
     const ScrambleJob a = device_job(j, 0), b = device_job(j, 1);
-    if (j.structured)
-        hipLaunchKernelGGL((scramble_rows_kernel<T, D, true>), grid, dim3(kScrThreads), 0, stream, a, b, j.perm,
-                           j.perm_batch_stride, B, j.H, j.G, j.L, members, tiles_per_slab, b_groups);
-    else
-        hipLaunchKernelGGL((scramble_rows_kernel<T, D, false>), grid, dim3(kScrThreads), 0, stream, a, b, j.perm,
-                           j.perm_batch_stride, B, j.H, j.G, j.L, members, tiles_per_slab, b_groups);
+#define FEDRAG_SCR_LAUNCH(ST_, QB_)                                                                              \
+    hipLaunchKernelGGL((scramble_rows_kernel<T, D, ST_, QB_>), grid, dim3(kScrThreads), 0, stream, a, b, j.perm, \
+                       j.perm_batch_stride, B, j.H, j.G, j.L, members, tiles_per_slab, b_groups)
+    if (j.structured) {
+        if (j.quant_bits == 8) FEDRAG_SCR_LAUNCH(true, 8);
+        else if (j.quant_bits == 4) FEDRAG_SCR_LAUNCH(true, 4);
+        else FEDRAG_SCR_LAUNCH(true, 0);
+    } else {
+        if (j.quant_bits == 8) FEDRAG_SCR_LAUNCH(false, 8);
+        else if (j.quant_bits == 4) FEDRAG_SCR_LAUNCH(false, 4);
+        else FEDRAG_SCR_LAUNCH(false, 0);
+    }
+#undef FEDRAG_SCR_LAUNCH
     return hipGetLastError();
 }
 

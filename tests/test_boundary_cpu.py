@@ -183,6 +183,38 @@ def test_codec_validation(lib):
         assert f(*a) == fb.OK
 
 
+def test_scramble_kv_quantized_validation(lib):
+    s = shape()
+    f = lib.fedrag_scramble_kv_quantized
+    ok = lambda: [ctypes.byref(s), 64, P(A), P(2 * A), P(3 * A), P(4 * A), P(5 * A), 1, 8, P(6 * A), P(7 * A), P(8 * A),
+                  P(9 * A), None]
+    for i in (0, 2, 3, 4, 5, 9, 10, 11, 12):
+        a = ok(); a[i] = None
+        assert f(*a) == fb.ERR_NULL
+    a = ok(); a[8] = 6
+    assert f(*a) == fb.ERR_UNSUPPORTED
+    s32 = shape(dt=fb.F32); a = ok(); a[0] = ctypes.byref(s32)
+    assert f(*a) == fb.ERR_UNSUPPORTED
+    a = ok(); a[9] = P(A)                       # codes over the input
+    assert f(*a) == fb.ERR_ALIAS
+    a = ok(); a[11] = P(6 * A)                  # both code buffers the same
+    assert f(*a) == fb.ERR_ALIAS
+    a = ok(); a[10] = P(7 * A + 4)              # params need 8-byte alignment
+    assert f(*a) == fb.ERR_ALIAS
+    a = ok(); a[7] = 3
+    assert f(*a) == fb.ERR_SHAPE
+    key = fb.StructuredKey(A, 2 * A, 3 * A, 4 * A)
+    g = lib.fedrag_scramble_kv_structured_quantized
+    okg = lambda: [ctypes.byref(s), 64, P(10 * A), P(11 * A), ctypes.byref(key), ctypes.byref(key), None, 0, 4,
+                   P(6 * A), P(7 * A), P(8 * A), P(9 * A), None]
+    a = okg(); a[4] = None
+    assert g(*a) == fb.ERR_NULL
+    a = okg(); a[8] = 16
+    assert g(*a) == fb.ERR_UNSUPPORTED
+    a = okg(); a[1] = 0
+    assert g(*a) == fb.OK
+
+
 def test_partial_attn_validation_and_workspace(lib):
     s = shape(B=16, Hq=32, Hkv=8)
     need = lib.fedrag_partial_attn_workspace_bytes(ctypes.byref(s), 1, 8192)

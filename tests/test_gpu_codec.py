@@ -88,3 +88,47 @@ def test_eight_bit_transport_with_and_without_s2(oracle):
           ", ".join(f"S2={'on' if k[0] else 'off'} {k[1]}-bit {100 * v:.2f} %" for k, v in errs.items()))
     assert errs[(False, 8)] < errs[(True, 8)]
     assert errs[(False, 8)] < 0.10 and errs[(True, 8)] > 0.25
+
+
+@pytest.mark.parametrize("bits", [8, 4])
+@pytest.mark.parametrize("dt,d,structured", [("bf16", 128, False), ("bf16", 128, True), ("f16", 64, False),
+                                              ("bf16", 64, True)])
+def test_scramble_with_codec_epilogue(oracle, bits, dt, d, structured):
+    """The fused call equals the two calls one after the other bit for bit, and both agree with the oracle's
+    composition up to the scramble's own one-ulp differences."""
+    dtype = W.torch_dtype(dt)
+    B, Hkv, L = 2, 2, 333
+    seed = 70 + bits + d
+    K = W.activations(B, Hkv, L, d, seed=seed, tensor_id=W.TID_K, outliers=True, dtype=dtype)
+    V = W.activations(B, Hkv, L, d, seed=seed, tensor_id=W.TID_V, outliers=True, dtype=dtype)
+    if structured:
+        ks = W.make_structured_keys(Hkv, d, 1, L, 1, seed=seed, dtype=dtype, n_perm=B, batch=B)
+        kk, kv = tuple(t.to(DEV) for t in ks.k), tuple(t.to(DEV) for t in ks.v)
+        perm = ks.perm_kv[0]
+        Ks, Vs = fb.fedrag_scramble_kv_structured(K.to(DEV), V.to(DEV), kk, kv, perm.to(DEV))
+        Kref = oracle.structured(K, ks.k, perm)
+    else:
+        keys = W.make_keys(Hkv, d, 1, L, 1, seed=seed, dtype=dtype, n_perm=B, batch=B)
+        kk, kv = keys.phi_k.to(DEV), keys.phi_v.to(DEV)
+        perm = keys.perm_kv[0]
+        Ks, Vs = fb.fedrag_scramble_kv(K.to(DEV), V.to(DEV), kk, kv, perm.to(DEV))
+        Kref = oracle.scramble(K, keys.phi_k, perm)
+    Kc, Kp, Vc, Vp = fb.fedrag_scramble_kv_quantized(K.to(DEV), V.to(DEV), kk, kv, perm.to(DEV), bits,
+                                                     structured=structured)
+    Kc2, Kp2 = fb.fedrag_quantize_rows(Ks, bits)
+    Vc2, Vp2 = fb.fedrag_quantize_rows(Vs, bits)
+    torch.cuda.synchronize()
+    assert torch.equal(Kc, Kc2) and torch.equal(Vc, Vc2)
+    assert torch.equal(Kp.view(torch.int32), Kp2.view(torch.int32)) and torch.equal(Vp.view(torch.int32), Vp2.view(torch.int32))
+    # against the oracle's composition: rows whose stored K' equals round(oracle) bit for bit must give equal codes
+    Kr = torch.from_numpy(Kref).to(dtype)
+    same_rows = (Ks.cpu() == Kr).all(dim=-1)
+    assert same_rows.float().mean() > 0.2
+    c_ref, p_ref = oracle.quantize_rows(Kr, bits)
+    assert np.array_equal(Kc.cpu().numpy()[same_rows.numpy()], c_ref[same_rows.numpy()])
+    assert np.array_equal(Kp.cpu().numpy()[same_rows.numpy()], p_ref[same_rows.numpy()])
+    # every row: dequantised values within one step (+ an ulp of K') of the oracle's composition
+    Kh = fb.fedrag_dequantize_rows(Kc, Kp, bits, dtype).cpu().double().numpy()
+    ref_h = oracle.dequantize_rows(c_ref, p_ref, bits).astype(np.float64)
+    step = p_ref[..., :1].astype(np.float64)
+    assert (np.abs(Kh - ref_h) <= 1.01 * step + 3 * PT.storage_ulp(ref_h, dtype)).all()
