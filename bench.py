@@ -380,7 +380,7 @@ def main():
         gbs = g["bytes"][name] / (t["avg_us"] * 1e-6) / 1e9
         per_call[name] = {"avg_us": round(t["avg_us"], 2), "calls_per_step": t["calls"] // args.steps,
                           "bytes": g["bytes"][name], "GB/s": round(gbs, 1), "frac_hbm": round(gbs / HBM_PEAK_GBS, 4)}
-    kernel_of = {"scramble_kv": "scramble_rows_kernel<BF16,128>", "partial_attn": "decode_attn_kernel<BF16,128>"}
+    kernel_of = {"scramble_kv": "scramble_rows_kernel<BF16,128,false,0>", "partial_attn": "decode_attn_kernel<BF16,128>"}
     dom = max(kernel_of, key=lambda n: calls[n]["total_ms"])
     roofline = {"bound": "hbm", "achieved": per_call[dom]["GB/s"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(per_call[dom]["GB/s"] / HBM_PEAK_GBS, 4), "traffic": MEASURED_TRAFFIC_BYTES.get(dom),
