@@ -267,6 +267,23 @@ def codec_leg(torch, fb, g, steps, warmup):
     us = timer.summary()["f"]["avg_us"]
     nb = 2 * n * (d * 2 + d + 8) + 4 * cfg.L_kv
     out["scramble_kv_quantized_8bit"] = {"avg_us": round(us, 2), "bytes": nb, "GB/s": round(nb / us / 1e3, 1)}
+    # the Compute Node's decode call reading the codes directly (one shard)
+    for bits in (8, 4):
+        Kc, Kp, Vc, Vp = fb.fedrag_scramble_kv_quantized(g["K"][0], g["V"][0], g["phi_k"], g["phi_v"], g["perm_kv"][0],
+                                                         bits, n_q_heads=cfg.n_q_heads)
+        call = lambda: fb.fedrag_partial_attn_quantized(g["Qs"], Kc, Kp, Vc, Vp, bits, None, O_part=g["O_parts"][0],
+                                                        lse=g["lses"][0], workspace=g["ws"])
+        for _ in range(warmup):
+            call()
+        torch.cuda.synchronize()
+        timer = CallTimer(torch)
+        for _ in range(steps):
+            timer.run("a", call)
+        torch.cuda.synchronize()
+        us = timer.summary()["a"]["avg_us"]
+        nb = 2 * n * (d * bits // 8 + 8)
+        out[f"partial_attn_quantized_{bits}bit"] = {"avg_us": round(us, 2), "bytes_read": nb,
+                                                    "GB/s": round(nb / us / 1e3, 1)}
     return out
 
 

@@ -240,6 +240,22 @@ fedrag_status fedrag_scramble_kv_structured_quantized(const fedrag_shape* shape,
                                                       uint8_t* K_codes, float* K_params,
                                                       uint8_t* V_codes, float* V_params, void* stream);
 
+/*
+ * fedrag_partial_attn on K', V' as they arrive through the transport codec (Section 7.5): the Compute Node reads
+ * the codes and dequantises them on the fly, so only d * bits / 8 + 8 bytes per key row are read instead of 2 d.
+ * Every element is reconstructed exactly as fedrag_dequantize_rows would (fp32 fma, one narrowing to the storage
+ * type), so the result equals fedrag_partial_attn(fedrag_dequantize_rows(...)) bit for bit.
+ * Qs : [B,Hq,L_q,d] storage type (16-bit);  K_codes, V_codes : uint8 [B,Hkv,L_kv,d*bits/8];
+ * K_params, V_params : fp32 [B,Hkv,L_kv,2] (8-byte aligned).  bits in {8, 4}.
+ * Only the decode shape is served: d_head = 128 and (n_q_heads / n_kv_heads) * L_q <= 16; anything else returns
+ * FEDRAG_ERR_UNSUPPORTED (dequantise, then call fedrag_partial_attn).  Workspace rule as fedrag_partial_attn.
+ */
+fedrag_status fedrag_partial_attn_quantized(const fedrag_shape* shape, int64_t L_q, int64_t L_kv, const void* Qs,
+                                            const uint8_t* K_codes, const float* K_params,
+                                            const uint8_t* V_codes, const float* V_params, int32_t bits,
+                                            float softmax_scale, float* O_part, float* lse,
+                                            void* workspace, size_t workspace_bytes, void* stream);
+
 /* inv_out[perm[j]] = j for j in [0, L): the gather array that undoes `perm`.  Device pointers. */
 fedrag_status fedrag_invert_perm(const int32_t* perm, int64_t L, int32_t* inv_out, void* stream);
 

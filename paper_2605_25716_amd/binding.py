@@ -23,7 +23,7 @@ EXPORTS = ("fedrag_scramble_kv", "fedrag_scramble_q", "fedrag_partial_attn",
            "fedrag_scramble_kv_structured", "fedrag_scramble_q_structured", "fedrag_unscramble_structured",
            "fedrag_local_attn", "fedrag_unpermute_lse", "fedrag_partial_attn_varlen", "fedrag_quantize_rows",
            "fedrag_dequantize_rows", "fedrag_scramble_kv_quantized", "fedrag_scramble_kv_structured_quantized",
-           "fedrag_invert_perm", "fedrag_status_string", "fedrag_version")
+           "fedrag_partial_attn_quantized", "fedrag_invert_perm", "fedrag_status_string", "fedrag_version")
 
 
 class Shape(ctypes.Structure):
@@ -82,6 +82,8 @@ def load() -> ctypes.CDLL:
         lib.fedrag_dequantize_rows.argtypes = [i64, i32, ctypes.c_int, i32, vp, vp, vp, vp]
         lib.fedrag_scramble_kv_quantized.argtypes = [sp, i64, vp, vp, vp, vp, vp, i32, i32, vp, vp, vp, vp, vp]
         lib.fedrag_scramble_kv_structured_quantized.argtypes = [sp, i64, vp, vp, kp, kp, vp, i32, i32, vp, vp, vp, vp, vp]
+        lib.fedrag_partial_attn_quantized.argtypes = [sp, i64, i64, vp, vp, vp, vp, vp, i32, ctypes.c_float, f32p, f32p,
+                                                      vp, ctypes.c_size_t, vp]
         lib.fedrag_invert_perm.argtypes = [vp, i64, vp, vp]
         lib.fedrag_status_string.argtypes = [ctypes.c_int]
         lib.fedrag_status_string.restype = ctypes.c_char_p
@@ -91,7 +93,7 @@ def load() -> ctypes.CDLL:
                      "fedrag_scramble_q_structured", "fedrag_unscramble_structured", "fedrag_local_attn",
                      "fedrag_unpermute_lse", "fedrag_partial_attn_varlen", "fedrag_quantize_rows",
                      "fedrag_dequantize_rows", "fedrag_scramble_kv_quantized",
-                     "fedrag_scramble_kv_structured_quantized"):
+                     "fedrag_scramble_kv_structured_quantized", "fedrag_partial_attn_quantized"):
             getattr(lib, name).restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -206,6 +208,29 @@ def fedrag_partial_attn_varlen(Qs, Ks, Vs, kv_lens, softmax_scale: Optional[floa
                                            _ptr(Vs) if L > 0 else None, _ptr(kv_lens), ctypes.c_float(softmax_scale),
                                            _ptr(O_part), _ptr(lse), _ptr(workspace), ws_bytes, _stream())
     _check(st, "fedrag_partial_attn_varlen")
+    return O_part, lse
+
+
+def fedrag_partial_attn_quantized(Qs, K_codes, K_params, V_codes, V_params, bits: int,
+                                  softmax_scale: Optional[float] = None, O_part=None, lse=None, workspace=None):
+    """fedrag_partial_attn reading K', V' as transport-codec codes (decode shapes, d = 128)."""
+    B, Hq, Lq, d = Qs.shape
+    Hkv, L = K_codes.shape[1], K_codes.shape[2]
+    shape = make_shape(B, Hq, Hkv, d, Qs.dtype)
+    if softmax_scale is None:
+        softmax_scale = float(d) ** -0.5
+    O_part = torch.empty((B, Hq, Lq, d), dtype=torch.float32, device=Qs.device) if O_part is None else O_part
+    lse = torch.empty((B, Hq, Lq), dtype=torch.float32, device=Qs.device) if lse is None else lse
+    need = int(load().fedrag_partial_attn_workspace_bytes(ctypes.byref(shape), Lq, L))
+    if workspace is None and need > 0:
+        workspace = torch.empty(need, dtype=torch.uint8, device=Qs.device)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    nz = L > 0
+    st = load().fedrag_partial_attn_quantized(ctypes.byref(shape), Lq, L, _ptr(Qs), _ptr(K_codes) if nz else None,
+                                              _ptr(K_params) if nz else None, _ptr(V_codes) if nz else None,
+                                              _ptr(V_params) if nz else None, bits, ctypes.c_float(softmax_scale),
+                                              _ptr(O_part), _ptr(lse), _ptr(workspace), ws_bytes, _stream())
+    _check(st, "fedrag_partial_attn_quantized")
     return O_part, lse
 
 

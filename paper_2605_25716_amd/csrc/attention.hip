@@ -126,6 +126,8 @@ int attn_kv_splits(int B, int Hq, int Hkv, int D, int dtype, int64_t Lq, int64_t
     return (int)((Lkv + per - 1) / per);
 }
 
+bool attn_uses_decode_kernel(int Hq, int Hkv, int64_t Lq) { return use_decode_kernel(Hq, Hkv, Lq); }
+
 int64_t decode_keys_per_split(int64_t Lkv, int n_splits) {
     int64_t per = (Lkv + n_splits - 1) / n_splits;
     return ((per + kDecStride - 1) / kDecStride) * kDecStride;
@@ -153,6 +155,11 @@ hipError_t launch_partial_attn(const AttnProblem& p_in, hipStream_t stream) {
     const int64_t rows = (int64_t)p.B * p.Hq * p.Lq;
     if (rows == 0) return hipSuccess;
     if (p.Lkv == 0) return launch_fill_empty(p.O, p.lse, rows, p.D, stream);
+    if (p.quant_bits != 0) {  // only the decode kernel reads the codec's codes
+        if (p.dtype == FEDRAG_F32 || p.causal || p.kv_lens || !use_decode_kernel(p.Hq, p.Hkv, p.Lq))
+            return hipErrorInvalidValue;
+        return launch_decode_attn(p, stream);
+    }
     if (p.dtype == FEDRAG_F32) return p.D == 128 ? launch_attn_f32<128>(p, stream) : launch_attn_f32<64>(p, stream);
     if (p.dtype != FEDRAG_BF16 && p.dtype != FEDRAG_F16) return hipErrorInvalidValue;
     return (!p.causal && use_decode_kernel(p.Hq, p.Hkv, p.Lq)) ? launch_decode_attn(p, stream)

@@ -34,11 +34,57 @@ __device__ __forceinline__ void transpose_keys_b16(const uint32_t (&in)[8][NC / 
     }
 }
 
-template <class T, int D>
+// One 32-key tile in registers.  QB = 0: K' rows as MFMA operands, V' rows as loaded.  QB = 8 or 4: the transport
+// codec's codes of the same elements (Section 7.5) plus the (scale, lo) of the rows this lane touches.
+template <class T, int D, int QB>
 struct DecTile {
     typename T::vec8 k[2][D / 32];
     uint32_t v[8][D / 32];
 };
+template <class T, int D>
+struct DecTile<T, D, 8> {
+    u32x2_t kc[2][D / 32];  // 8 codes per (16-key tile, contraction step)
+    u32x2_t vc[8];          // 8 codes per key (D = 128: DCH = 8 elements per lane and key)
+    u32x2_t kp[2];          // (scale, lo) as bits, of key rows 16 mt + lr
+    u32x2_t vp[8];          // of this lane's eight keys
+};
+template <class T, int D>
+struct DecTile<T, D, 4> {
+    uint32_t kc[2][D / 32];
+    uint32_t vc[8];
+    u32x2_t kp[2];
+    u32x2_t vp[8];
+};
+
+// 8 codes -> 8 storage-type values, exactly as dequantize_rows_kernel produces them: fma(code, scale, lo) in fp32,
+// narrowed once.  (The fp32 value is pinned so that the two roundings are not folded into one.)
+template <class T>
+__device__ __forceinline__ typename T::vec8 dequant_codes(const uint32_t (&q)[8], u32x2_t prm) {
+    const uint32_t scale_bits = prm[0], lo_bits = prm[1];  // (bit-casting a vector element in place picks element 0)
+    const float scale = __builtin_bit_cast(float, scale_bits), lo = __builtin_bit_cast(float, lo_bits);
+    typename T::vec8 out;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        float x = __builtin_fmaf((float)q[e], scale, lo);
+        pin_here(x);
+        out[e] = T::from_float(x);
+    }
+    return out;
+}
+template <class T>
+__device__ __forceinline__ typename T::vec8 dequant8(u32x2_t w, u32x2_t prm) {  // 8-bit codes
+    uint32_t q[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) q[e] = (w[e / 4] >> (8 * (e % 4))) & 255u;
+    return dequant_codes<T>(q, prm);
+}
+template <class T>
+__device__ __forceinline__ typename T::vec8 dequant8(uint32_t w, u32x2_t prm) {  // 4-bit codes
+    uint32_t q[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) q[e] = (w >> (4 * e)) & 15u;
+    return dequant_codes<T>(q, prm);
+}
 
 #ifndef FEDRAG_DEC_NBUF
 #define FEDRAG_DEC_NBUF 2   // register tile sets per wave
@@ -50,21 +96,24 @@ struct DecTile {
 #define FEDRAG_DEC_AUX 2    // cache-policy bits of the streaming loads: non-temporal (K'/V' are read once)
 #endif
 
-template <class T, int D>
+template <class T, int D, int QB>
 __global__ __launch_bounds__(kDecThreads, FEDRAG_DEC_OCC) void decode_attn_kernel(const typename T::elem* __restrict__ Q,
-                                                                     const typename T::elem* __restrict__ K,
-                                                                     const typename T::elem* __restrict__ V, int R,
+                                                                     const void* __restrict__ K,
+                                                                     const void* __restrict__ V,
+                                                                     const float* __restrict__ Kprm,
+                                                                     const float* __restrict__ Vprm, int R,
                                                                      int64_t L, int n_splits, int64_t keys_per_split,
                                                                      float scale_log2, float* __restrict__ O,
                                                                      float* __restrict__ lse, int64_t total_rows,
                                                                      const int32_t* __restrict__ kv_lens, int Hkv) {
     typedef typename T::elem elem;
     typedef typename T::vec8 vec8;
-    typedef DecTile<T, D> Tile;
+    typedef DecTile<T, D, QB> Tile;
+    static_assert(QB == 0 || D == 128, "the quantised path is laid out for d = 128");
     constexpr int KS = D / 32;   // contraction steps of the first product
     constexpr int DCH = D / 16;  // elements per lane per key of V' (= number of 16-row tiles of O^T)
     constexpr int NW = DCH / 2;  // 32-bit words of that
-    constexpr int ROWB = D * 2;  // bytes per row
+    constexpr int ROWB = QB ? D * QB / 8 : D * 2;  // bytes per row of K' / V' as stored (values, or codes)
     constexpr int TILEB = kDecTile * ROWB;
     constexpr int NBUF = FEDRAG_DEC_NBUF;
     constexpr int AUX = FEDRAG_DEC_AUX;
@@ -93,8 +142,8 @@ __global__ __launch_bounds__(kDecThreads, FEDRAG_DEC_OCC) void decode_attn_kerne
     if (k_end < k_begin) k_end = k_begin;
 
     const elem* Qu = Q + unit * R * D;
-    const char* Kb = (const char*)(K + unit * L * D);
-    const char* Vb = (const char*)(V + unit * L * D);
+    const char* Kb = (const char*)K + unit * L * ROWB;
+    const char* Vb = (const char*)V + unit * L * ROWB;
 
     // Q'^T operands: column lr (query), contraction slice 32 ks + 8 lq; padding queries are zero
     vec8 qop[KS];
@@ -108,8 +157,9 @@ __global__ __launch_bounds__(kDecThreads, FEDRAG_DEC_OCC) void decode_attn_kerne
     float m_run = -INFINITY, l_run = 0.f;
 
     // per-lane byte offsets inside a 32-key tile (the tile base is wave-uniform)
-    const uint32_t koff = (uint32_t)(lr * ROWB + lq * 16);
-    const uint32_t voff = (uint32_t)(lq * 4 * ROWB + lr * DCH * 2);
+    constexpr int EB = QB ? QB : 16;  // bits per stored element
+    const uint32_t koff = (uint32_t)(lr * ROWB + lq * EB);          // 8 elements per lane and contraction step
+    const uint32_t voff = (uint32_t)(lq * 4 * ROWB + lr * DCH * EB / 8);
 
     // Streaming loads go through buffer resources based at the split's first key: the address is
     // (scalar resource base) + (scalar tile offset) + (per-lane 32-bit offset), one VGPR per lane in total.
@@ -118,21 +168,41 @@ __global__ __launch_bounds__(kDecThreads, FEDRAG_DEC_OCC) void decode_attn_kerne
         __builtin_amdgcn_make_buffer_rsrc((void*)(Kb + k_begin * ROWB), 0, (int)split_bytes, 0x00020000);
     const __amdgpu_buffer_rsrc_t rv =
         __builtin_amdgcn_make_buffer_rsrc((void*)(Vb + k_begin * ROWB), 0, (int)split_bytes, 0x00020000);
+    // quantised path: the (scale, lo) pairs of the split's rows, 8 bytes per key
+    const int64_t n_split_keys = k_end - k_begin;
+    const __amdgpu_buffer_rsrc_t rkp = __builtin_amdgcn_make_buffer_rsrc(
+        (void*)(QB ? Kprm + (unit * L + k_begin) * 2 : nullptr), 0, QB ? (int)(n_split_keys * 8) : 0, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rvp = __builtin_amdgcn_make_buffer_rsrc(
+        (void*)(QB ? Vprm + (unit * L + k_begin) * 2 : nullptr), 0, QB ? (int)(n_split_keys * 8) : 0, 0x00020000);
     auto load_k = [&](int tile, Tile& t) {  // tile index inside the split; all 32 keys exist
         const int soff = tile * TILEB;
 #pragma unroll
-        for (int mt = 0; mt < 2; ++mt)
+        for (int mt = 0; mt < 2; ++mt) {
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks)
-                t.k[mt][ks] = __builtin_bit_cast(
-                    vec8, __builtin_amdgcn_raw_buffer_load_b128(rk, (int)koff + mt * 16 * ROWB + ks * 64, soff, AUX));
+            for (int ks = 0; ks < KS; ++ks) {
+                const int off = (int)koff + mt * 16 * ROWB + ks * 4 * EB;
+                if constexpr (QB == 0)
+                    t.k[mt][ks] = __builtin_bit_cast(vec8, __builtin_amdgcn_raw_buffer_load_b128(rk, off, soff, AUX));
+                else if constexpr (QB == 8)
+                    t.kc[mt][ks] = __builtin_amdgcn_raw_buffer_load_b64(rk, off, soff, AUX);
+                else
+                    t.kc[mt][ks] = __builtin_amdgcn_raw_buffer_load_b32(rk, off, soff, AUX);
+            }
+            if constexpr (QB != 0)
+                t.kp[mt] = __builtin_amdgcn_raw_buffer_load_b64(rkp, (mt * 16 + lr) * 8, tile * kDecTile * 8, 0);
+        }
     };
     auto load_v = [&](int tile, Tile& t) {
         const int soff = tile * TILEB;
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
             const int off = (int)voff + ((e / 4) * 16 + (e % 4)) * ROWB;
-            if constexpr (NW == 4) {
+            if constexpr (QB != 0) {
+                if constexpr (QB == 8) t.vc[e] = __builtin_amdgcn_raw_buffer_load_b64(rv, off, soff, AUX);
+                else t.vc[e] = __builtin_amdgcn_raw_buffer_load_b32(rv, off, soff, AUX);
+                t.vp[e] = __builtin_amdgcn_raw_buffer_load_b64(rvp, ((e / 4) * 16 + (e % 4) + lq * 4) * 8,
+                                                               tile * kDecTile * 8, 0);
+            } else if constexpr (NW == 4) {
                 const u32x4_t w = __builtin_amdgcn_raw_buffer_load_b128(rv, off, soff, AUX);
                 t.v[e][0] = w[0]; t.v[e][1] = w[1]; t.v[e][2] = w[2]; t.v[e][3] = w[3];
             } else {
@@ -147,15 +217,27 @@ __global__ __launch_bounds__(kDecThreads, FEDRAG_DEC_OCC) void decode_attn_kerne
             int64_t key = key0 + mt * 16 + lr;
             if (key >= L) key = L - 1;
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) t.k[mt][ks] = *(const vec8*)(Kb + key * ROWB + ks * 64 + lq * 16);
+            for (int ks = 0; ks < KS; ++ks) {
+                const char* p = Kb + key * ROWB + ks * 4 * EB + lq * EB;
+                if constexpr (QB == 0) t.k[mt][ks] = *(const vec8*)p;
+                else if constexpr (QB == 8) t.kc[mt][ks] = *(const u32x2_t*)p;
+                else t.kc[mt][ks] = *(const uint32_t*)p;
+            }
+            if constexpr (QB != 0) t.kp[mt] = *(const u32x2_t*)(Kprm + (unit * L + key) * 2);
         }
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
             int64_t key = key0 + (e / 4) * 16 + lq * 4 + (e % 4);
             if (key >= L) key = L - 1;
-            const uint32_t* p = (const uint32_t*)(Vb + key * ROWB + lr * DCH * 2);
+            const char* p = Vb + key * ROWB + lr * DCH * EB / 8;
+            if constexpr (QB == 0) {
 #pragma unroll
-            for (int w = 0; w < NW; ++w) t.v[e][w] = p[w];
+                for (int w = 0; w < NW; ++w) t.v[e][w] = ((const uint32_t*)p)[w];
+            } else {
+                if constexpr (QB == 8) t.vc[e] = *(const u32x2_t*)p;
+                else t.vc[e] = *(const uint32_t*)p;
+                t.vp[e] = *(const u32x2_t*)(Vprm + (unit * L + key) * 2);
+            }
         }
     };
 
@@ -168,7 +250,12 @@ __global__ __launch_bounds__(kDecThreads, FEDRAG_DEC_OCC) void decode_attn_kerne
         for (int mt = 0; mt < 2; ++mt) {
             s[mt] = zero_vec<f32x4_t>();
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) s[mt] = T::mfma16(t.k[mt][ks], qop[ks], s[mt]);
+            for (int ks = 0; ks < KS; ++ks) {
+                vec8 kop;
+                if constexpr (QB == 0) kop = t.k[mt][ks];
+                else kop = dequant8<T>(t.kc[mt][ks], t.kp[mt]);
+                s[mt] = T::mfma16(kop, qop[ks], s[mt]);
+            }
         }
         if (reload) load_k(next_tile, t);
         float p[8];
@@ -200,7 +287,18 @@ __global__ __launch_bounds__(kDecThreads, FEDRAG_DEC_OCC) void decode_attn_kerne
         m_run = m_new;
         // second product in two halves of the d-rows to keep the transposed operands short-lived
         u32x4_t vt[DCH];
-        transpose_keys_b16<DCH>(t.v, vt);
+        if constexpr (QB == 0) {
+            transpose_keys_b16<DCH>(t.v, vt);
+        } else {
+            uint32_t v16[8][DCH / 2];  // the eight keys' rows in the storage type, as the unquantised path loads them
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const u32x4_t w = __builtin_bit_cast(u32x4_t, dequant8<T>(t.vc[e], t.vp[e]));
+#pragma unroll
+                for (int c = 0; c < DCH / 2; ++c) v16[e][c] = w[c];
+            }
+            transpose_keys_b16<DCH>(v16, vt);
+        }
         if (reload) load_v(next_tile, t);
 #pragma unroll
         for (int i = 0; i < DCH; ++i) {
@@ -284,7 +382,7 @@ __global__ __launch_bounds__(kDecThreads, FEDRAG_DEC_OCC) void decode_attn_kerne
     }
 }
 
-template <class T, int D>
+template <class T, int D, int QB>
 static hipError_t launch_decode_t(const AttnProblem& p, hipStream_t stream) {
     typedef typename T::elem elem;
     const float scale_log2 = p.scale * kLog2e;
@@ -299,18 +397,24 @@ static hipError_t launch_decode_t(const AttnProblem& p, hipStream_t stream) {
         Odst = (float*)p.workspace;
         Ldst = Odst + (size_t)splits * rows * D;
     }
-    hipLaunchKernelGGL((decode_attn_kernel<T, D>), dim3((unsigned)(units * splits)), dim3(kDecThreads), 0, stream,
-                       (const elem*)p.Q, (const elem*)p.K, (const elem*)p.V, R, p.Lkv, splits, per, scale_log2, Odst,
-                       Ldst, rows, p.kv_lens, p.Hkv);
+    hipLaunchKernelGGL((decode_attn_kernel<T, D, QB>), dim3((unsigned)(units * splits)), dim3(kDecThreads), 0, stream,
+                       (const elem*)p.Q, p.K, p.V, p.K_params, p.V_params, R, p.Lkv, splits, per, scale_log2, Odst, Ldst,
+                       rows, p.kv_lens, p.Hkv);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || splits == 1) return e;
     return launch_lse_merge(Odst, Ldst, splits, rows, D, p.O, p.lse, stream);
 }
 
 hipError_t launch_decode_attn(const AttnProblem& p, hipStream_t stream) {
+    if (p.quant_bits != 0) {  // codes of the transport codec in place of K', V' (d = 128, checked by the caller)
+        if (p.D != 128) return hipErrorInvalidValue;
+        if (p.dtype == FEDRAG_BF16)
+            return p.quant_bits == 8 ? launch_decode_t<BF16, 128, 8>(p, stream) : launch_decode_t<BF16, 128, 4>(p, stream);
+        return p.quant_bits == 8 ? launch_decode_t<F16, 128, 8>(p, stream) : launch_decode_t<F16, 128, 4>(p, stream);
+    }
     if (p.dtype == FEDRAG_BF16)
-        return p.D == 128 ? launch_decode_t<BF16, 128>(p, stream) : launch_decode_t<BF16, 64>(p, stream);
-    return p.D == 128 ? launch_decode_t<F16, 128>(p, stream) : launch_decode_t<F16, 64>(p, stream);
+        return p.D == 128 ? launch_decode_t<BF16, 128, 0>(p, stream) : launch_decode_t<BF16, 64, 0>(p, stream);
+    return p.D == 128 ? launch_decode_t<F16, 128, 0>(p, stream) : launch_decode_t<F16, 64, 0>(p, stream);
 }
 
 }  // namespace fedrag

@@ -40,6 +40,9 @@ struct AttnProblem {
     int64_t Lq, Lkv;
     const void *Q, *K, *V;
     float scale;
+    int quant_bits;          // 0, or 8 / 4: K, V hold the transport codec's codes and K_params, V_params their
+    const float* K_params;   //   per-row (scale, lo), [B,Hkv,Lkv,2] (decode shapes, 16-bit dtype, D = 128 only)
+    const float* V_params;
     const int32_t* kv_lens;  // NULL, or [B] device array: sequence b has only its first kv_lens[b] keys (<= Lkv)
     bool causal;  // the Lq queries are the last Lq of the Lkv tokens and see nothing after themselves
     float* O;     // [B,Hq,Lq,D]
@@ -49,6 +52,7 @@ struct AttnProblem {
 };
 // How the launcher will split the shard's keys across workgroups (1 = no workspace needed).
 int attn_kv_splits(int B, int Hq, int Hkv, int D, int dtype, int64_t Lq, int64_t Lkv);
+bool attn_uses_decode_kernel(int Hq, int Hkv, int64_t Lq);  // G * Lq <= 16: the HBM-bound streaming kernel
 size_t attn_workspace_bytes(int B, int Hq, int Hkv, int D, int dtype, int64_t Lq, int64_t Lkv);
 hipError_t launch_partial_attn(const AttnProblem& p, hipStream_t stream);
 

@@ -132,3 +132,52 @@ def test_scramble_with_codec_epilogue(oracle, bits, dt, d, structured):
     ref_h = oracle.dequantize_rows(c_ref, p_ref, bits).astype(np.float64)
     step = p_ref[..., :1].astype(np.float64)
     assert (np.abs(Kh - ref_h) <= 1.01 * step + 3 * PT.storage_ulp(ref_h, dtype)).all()
+
+
+ATTN_Q_CASES = [
+    # name, B, Hq, Hkv, Lq, L, dtype
+    ("g4_L3000", 3, 8, 2, 1, 3000, "bf16"),        # several KV splits, ragged tail
+    ("g8_L517", 2, 16, 2, 1, 517, "bf16"),
+    ("rows16_L95", 1, 8, 2, 4, 95, "f16"),         # G * Lq = 16, fp16 (the two-rounding reconstruction matters)
+    ("one_key", 1, 4, 1, 1, 1, "bf16"),
+]
+
+
+@pytest.mark.parametrize("bits", [8, 4])
+@pytest.mark.parametrize("case", ATTN_Q_CASES, ids=[c[0] for c in ATTN_Q_CASES])
+def test_partial_attn_on_codes(oracle, case, bits):
+    name, B, Hq, Hkv, Lq, L, dt = case
+    d = 128
+    dtype = W.torch_dtype(dt)
+    seed = 800 + len(name) + bits
+    keys = W.make_keys(Hkv, d, Lq, L, 1, seed=seed, dtype=dtype)
+    rnd = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dtype)
+    mk = lambda H, n, tid: W.activations(B, H, n, d, seed=seed, tensor_id=tid, outliers=True, dtype=dtype)
+    Qs = rnd(oracle.scramble(mk(Hq, Lq, W.TID_Q), keys.phi_q, None))
+    Ks = rnd(oracle.scramble(mk(Hkv, L, W.TID_K), keys.phi_k, keys.perm_kv[0]))
+    Vs = rnd(oracle.scramble(mk(Hkv, L, W.TID_V), keys.phi_v, keys.perm_kv[0]))
+    # codes and parameters from the ORACLE, so that both sides start from identical bits
+    kc, kp = oracle.quantize_rows(Ks, bits)
+    vc, vp = oracle.quantize_rows(Vs, bits)
+    t = lambda a: torch.from_numpy(a).to(DEV)
+    O, lse = fb.fedrag_partial_attn_quantized(Qs.to(DEV), t(kc), t(kp), t(vc), t(vp), bits)
+    # the oracle's composition: reconstruct (fp32), narrow once to the storage type, attend
+    Kh = torch.from_numpy(oracle.dequantize_rows(kc, kp, bits)).to(dtype)
+    Vh = torch.from_numpy(oracle.dequantize_rows(vc, vp, bits)).to(dtype)
+    Or, lr = oracle.partial_attn(Qs, Kh, Vh)
+    PT.check_attn(O, lse, Or, lr, dtype, name)
+    # and the library's own two calls one after the other give the same bits as the fused call
+    Kd = fb.fedrag_dequantize_rows(t(kc), t(kp), bits, dtype)
+    Vd = fb.fedrag_dequantize_rows(t(vc), t(vp), bits, dtype)
+    O2, lse2 = fb.fedrag_partial_attn(Qs.to(DEV), Kd, Vd)
+    torch.cuda.synchronize()
+    assert torch.equal(O, O2) and torch.equal(lse, lse2)
+
+
+def test_partial_attn_on_codes_rejects_other_shapes():
+    Q = torch.zeros((1, 8, 64, 128), dtype=torch.bfloat16, device=DEV)       # prefill shape
+    c = torch.zeros((1, 2, 64, 128), dtype=torch.uint8, device=DEV)
+    p = torch.zeros((1, 2, 64, 2), dtype=torch.float32, device=DEV)
+    with pytest.raises(fb.FedragError) as e:
+        fb.fedrag_partial_attn_quantized(Q, c, p, c, p, 8)
+    assert e.value.status == fb.ERR_UNSUPPORTED
