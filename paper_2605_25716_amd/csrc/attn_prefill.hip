@@ -72,9 +72,11 @@ __global__ __launch_bounds__(kPreThreads, 1) void prefill_attn_kernel(const type
     const int unit = xcd + 8 * (slot / per_unit);
     if (unit >= n_units) return;
     const int w_in_unit = slot % per_unit;
-    const int hg = w_in_unit / q_tiles;
-    // CAUSAL: later query tiles visit more keys; hand them out first so the short ones fill the tail of the launch
-    const int qt = CAUSAL ? q_tiles - 1 - w_in_unit % q_tiles : w_in_unit % q_tiles;
+    // CAUSAL: later query tiles visit more keys.  Hand out the last tile of every head of the group first, then the
+    // one before it, and so on: workgroups are started in index order as compute units free up, so every compute
+    // unit ends up with a long tile followed by short ones and the launch does not wait on a late long tile.
+    const int hg = CAUSAL ? w_in_unit % G : w_in_unit / q_tiles;
+    const int qt = CAUSAL ? q_tiles - 1 - w_in_unit / G : w_in_unit % q_tiles;
     const int b = unit / Hkv;
     const int g = unit % Hkv;
     const int h = g * G + hg;
