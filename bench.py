@@ -212,7 +212,7 @@ def rerank_leg(torch, W, fb, dev, steps, warmup):
     kv = torch.tensor(lens, dtype=torch.int32, device=dev)
     O = torch.empty((B, H, Lmax, d), dtype=torch.float32, device=dev)
     lse = torch.empty((B, H, Lmax), dtype=torch.float32, device=dev)
-    call = lambda: fb.fedrag_partial_attn_varlen(Qs, Ks, Vs, kv, None, O_part=O, lse=lse)
+    call = lambda: fb.fedrag_partial_attn_varlen(Qs, Ks, Vs, kv, None, O_part=O, lse=lse, q_lens=kv)
     for _ in range(warmup):
         call()
     torch.cuda.synchronize()

@@ -108,13 +108,15 @@ size_t fedrag_partial_attn_workspace_bytes(const fedrag_shape* shape, int64_t L_
  * re-ranker scores several query-document pairs at once, each a sequence of its own): sequence b attends to its
  * first kv_lens[b] keys only; rows of Ks, Vs past that are never used in the result and may hold anything.
  * kv_lens : int32 [B], DEVICE memory, 0 <= kv_lens[b] <= L_kv (values outside are clamped into that range);
- * a sequence with 0 keys returns O_part = 0, lse = -inf.  All L_q query rows of every sequence are computed
- * (padding query rows give finite, meaningless rows).  Everything else, including the workspace size for
- * (L_q, L_kv), as fedrag_partial_attn.
+ * a sequence with 0 keys returns O_part = 0, lse = -inf.
+ * q_lens  : NULL, or int32 [B], DEVICE memory: sequence b has q_lens[b] real query rows (clamped to [0, L_q]); the
+ * rows after them are padding and are NOT written (O_part, lse keep what they held) and, when L_q is large, not
+ * computed.  With NULL all L_q rows of every sequence are computed (padding rows give finite, meaningless rows).
+ * Everything else, including the workspace size for (L_q, L_kv), as fedrag_partial_attn.
  */
 fedrag_status fedrag_partial_attn_varlen(const fedrag_shape* shape, int64_t L_q, int64_t L_kv,
                                          const void* Qs, const void* Ks, const void* Vs,
-                                         const int32_t* kv_lens, float softmax_scale,
+                                         const int32_t* kv_lens, const int32_t* q_lens, float softmax_scale,
                                          float* O_part, float* lse,
                                          void* workspace, size_t workspace_bytes, void* stream);
 

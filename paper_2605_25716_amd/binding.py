@@ -67,7 +67,7 @@ def load() -> ctypes.CDLL:
         lib.fedrag_partial_attn.argtypes = [sp, i64, i64, vp, vp, vp, ctypes.c_float, f32p, f32p, vp,
                                             ctypes.c_size_t, vp]
         lib.fedrag_local_attn.argtypes = lib.fedrag_partial_attn.argtypes
-        lib.fedrag_partial_attn_varlen.argtypes = [sp, i64, i64, vp, vp, vp, vp, ctypes.c_float, f32p, f32p, vp,
+        lib.fedrag_partial_attn_varlen.argtypes = [sp, i64, i64, vp, vp, vp, vp, vp, ctypes.c_float, f32p, f32p, vp,
                                                    ctypes.c_size_t, vp]
         lib.fedrag_unpermute_lse.argtypes = [sp, i64, f32p, vp, f32p, vp]
         lib.fedrag_partial_attn_workspace_bytes.argtypes = [sp, i64, i64]
@@ -189,7 +189,7 @@ def fedrag_partial_attn(Qs, Ks, Vs, softmax_scale: Optional[float] = None, O_par
 
 
 def fedrag_partial_attn_varlen(Qs, Ks, Vs, kv_lens, softmax_scale: Optional[float] = None, O_part=None, lse=None,
-                               workspace=None):
+                               workspace=None, q_lens=None):
     """fedrag_partial_attn over a padded batch: sequence b attends to its first kv_lens[b] keys.  kv_lens int32 [B]."""
     B, Hq, Lq, d = Qs.shape
     Hkv, L = Ks.shape[1], Ks.shape[2]
@@ -205,7 +205,8 @@ def fedrag_partial_attn_varlen(Qs, Ks, Vs, kv_lens, softmax_scale: Optional[floa
         workspace = torch.empty(need, dtype=torch.uint8, device=Qs.device)
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     st = load().fedrag_partial_attn_varlen(ctypes.byref(shape), Lq, L, _ptr(Qs), _ptr(Ks) if L > 0 else None,
-                                           _ptr(Vs) if L > 0 else None, _ptr(kv_lens), ctypes.c_float(softmax_scale),
+                                           _ptr(Vs) if L > 0 else None, _ptr(kv_lens), _ptr(q_lens),
+                                           ctypes.c_float(softmax_scale),
                                            _ptr(O_part), _ptr(lse), _ptr(workspace), ws_bytes, _stream())
     _check(st, "fedrag_partial_attn_varlen")
     return O_part, lse

@@ -16,7 +16,8 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const float* __restrict__
                                                        const float* __restrict__ V, int Hq, int Hkv, int64_t Lq,
                                                        int64_t Lkv, int causal, int64_t total_rows, float scale,
                                                        float* __restrict__ O, float* __restrict__ lse,
-                                                       const int32_t* __restrict__ kv_lens) {
+                                                       const int32_t* __restrict__ kv_lens,
+                                                       const int32_t* __restrict__ q_lens) {
     constexpr int CPL = D / kWave;  // output columns per lane
     __shared__ float qs[4][D];
     const int wave = threadIdx.x / kWave;
@@ -27,6 +28,7 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const float* __restrict__
     const int b = (int)(bh / Hq);
     const int h = (int)(bh % Hq);
     const int g = h / (Hq / Hkv);
+    if (q_lens && (row % Lq) >= q_lens[b]) return;  // padding query row of a shorter sequence: not computed
     const float* q = Q + row * D;
     const float* Kg = K + ((int64_t)b * Hkv + g) * Lkv * D;
     const float* Vg = V + ((int64_t)b * Hkv + g) * Lkv * D;
@@ -145,7 +147,7 @@ static hipError_t launch_attn_f32(const AttnProblem& p, hipStream_t stream) {
     const int64_t rows = (int64_t)p.B * p.Hq * p.Lq;
     hipLaunchKernelGGL(attn_f32_kernel<D>, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, stream, (const float*)p.Q,
                        (const float*)p.K, (const float*)p.V, p.Hq, p.Hkv, p.Lq, p.Lkv, p.causal ? 1 : 0, rows, p.scale,
-                       p.O, p.lse, p.kv_lens);
+                       p.O, p.lse, p.kv_lens, p.q_lens);
     return hipGetLastError();
 }
 

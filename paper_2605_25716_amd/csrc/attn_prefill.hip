@@ -47,7 +47,8 @@ __global__ __launch_bounds__(kPreThreads, 1) void prefill_attn_kernel(const type
                                                                       const typename T::elem* __restrict__ K,
                                                                       const typename T::elem* __restrict__ V, int Hq,
                                                                       int Hkv, int64_t Lq, int64_t L_stride,
-                                                                      const int32_t* __restrict__ kv_lens, int q_tiles,
+                                                                      const int32_t* __restrict__ kv_lens,
+                                                                      const int32_t* __restrict__ q_lens, int q_tiles,
                                                                       int n_units, float scale_log2,
                                                                       float* __restrict__ O, float* __restrict__ lse) {
     typedef typename T::elem elem;
@@ -96,12 +97,19 @@ __global__ __launch_bounds__(kPreThreads, 1) void prefill_attn_kernel(const type
         const int64_t v = kv_lens[b];
         L = v < 0 ? 0 : (v < L_stride ? v : L_stride);
     }
+    // query rows of this sequence that exist (padded batch): rows past them are neither computed nor written
+    int64_t Lq_rows = Lq;
+    if (q_lens) {
+        const int64_t v = q_lens[b];
+        Lq_rows = v < 0 ? 0 : (v < Lq ? v : Lq);
+    }
+    if ((int64_t)qt * kPreQTile >= Lq_rows) return;  // workgroup-uniform, before any barrier
     float* Oh = O + ((int64_t)b * Hq + h) * Lq * D;
     float* Lh = lse + ((int64_t)b * Hq + h) * Lq;
 
     const int64_t q_row = (int64_t)qt * kPreQTile + wave * kPreQ + li;  // this lane's query row
     if (L == 0) {  // no keys (workgroup-uniform, before any barrier): O = 0, lse = -inf
-        if (q_row < Lq) {
+        if (q_row < Lq_rows) {
             for (int c = lh * (D / 2); c < (lh + 1) * (D / 2); c += 4) *(f32x4_t*)(Oh + q_row * D + c) = zero_vec<f32x4_t>();
             if (lh == 0) Lh[q_row] = -INFINITY;
         }
@@ -374,7 +382,7 @@ __global__ __launch_bounds__(kPreThreads, 1) void prefill_attn_kernel(const type
     // epilogue: lane holds query li and rows d = 32 i + 8 (r / 4) + 4 lh + r % 4 of O^T
     const float l_tot = xor32_sum(l_run);
     const float inv = (l_tot > 0.f) ? 1.0f / l_tot : 0.f;
-    if (q_row < Lq) {
+    if (q_row < Lq_rows) {
 #pragma unroll
         for (int i = 0; i < MT; ++i)
 #pragma unroll
@@ -397,7 +405,7 @@ static hipError_t launch_prefill_t(const AttnProblem& p, hipStream_t stream) {
     const int per_unit = (p.Hq / p.Hkv) * q_tiles;
     const int64_t grid = (int64_t)8 * ((n_units + 7) / 8) * per_unit;
     hipLaunchKernelGGL((prefill_attn_kernel<T, D, CAUSAL>), dim3((unsigned)grid), dim3(kPreThreads), 0,
-                       stream, (const elem*)p.Q, (const elem*)p.K, (const elem*)p.V, p.Hq, p.Hkv, p.Lq, p.Lkv, p.kv_lens, q_tiles,
+                       stream, (const elem*)p.Q, (const elem*)p.K, (const elem*)p.V, p.Hq, p.Hkv, p.Lq, p.Lkv, p.kv_lens, p.q_lens, q_tiles,
                        n_units, scale_log2, p.O, p.lse);
     return hipGetLastError();
 }

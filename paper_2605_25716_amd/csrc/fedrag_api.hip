@@ -158,9 +158,9 @@ fedrag_status fedrag_partial_attn(const fedrag_shape* shape, int64_t L_q, int64_
 }
 
 fedrag_status fedrag_partial_attn_varlen(const fedrag_shape* shape, int64_t L_q, int64_t L_kv, const void* Qs,
-                                         const void* Ks, const void* Vs, const int32_t* kv_lens, float softmax_scale,
-                                         float* O_part, float* lse, void* workspace, size_t workspace_bytes,
-                                         void* stream) {
+                                         const void* Ks, const void* Vs, const int32_t* kv_lens,
+                                         const int32_t* q_lens, float softmax_scale, float* O_part, float* lse,
+                                         void* workspace, size_t workspace_bytes, void* stream) {
     fedrag_status st = check_shape(shape, true);
     if (st != FEDRAG_OK) return st;
     if (L_q < 0 || L_kv < 0 || L_q > INT32_MAX || L_kv > INT32_MAX) return FEDRAG_ERR_SHAPE;
@@ -172,7 +172,8 @@ fedrag_status fedrag_partial_attn_varlen(const fedrag_shape* shape, int64_t L_q,
         return FEDRAG_ERR_SHAPE;
     if (!(softmax_scale > 0.0f) || softmax_scale - softmax_scale != 0.0f) return FEDRAG_ERR_SHAPE;  // finite, > 0
     if (!aligned16(Qs) || !aligned16(Ks) || !aligned16(Vs) || !aligned16(O_part) ||
-        (reinterpret_cast<uintptr_t>(lse) & 3u) || (reinterpret_cast<uintptr_t>(kv_lens) & 3u) || !aligned16(workspace))
+        (reinterpret_cast<uintptr_t>(lse) & 3u) || (reinterpret_cast<uintptr_t>(kv_lens) & 3u) ||
+        (reinterpret_cast<uintptr_t>(q_lens) & 3u) || !aligned16(workspace))
         return FEDRAG_ERR_ALIAS;
     const size_t need = attn_workspace_bytes(shape->batch, shape->n_q_heads, shape->n_kv_heads, shape->d_head,
                                              shape->dtype, L_q, L_kv);
@@ -183,6 +184,7 @@ fedrag_status fedrag_partial_attn_varlen(const fedrag_shape* shape, int64_t L_q,
     p.Lq = L_q; p.Lkv = L_kv;
     p.Q = Qs; p.K = Ks; p.V = Vs;
     p.kv_lens = kv_lens;
+    p.q_lens = q_lens;
     p.scale = softmax_scale;
     p.O = O_part; p.lse = lse;
     p.workspace = workspace; p.workspace_bytes = workspace_bytes;

@@ -44,6 +44,8 @@ struct AttnProblem {
     const float* K_params;   //   per-row (scale, lo), [B,Hkv,Lkv,2] (decode shapes, 16-bit dtype, D = 128 only)
     const float* V_params;
     const int32_t* kv_lens;  // NULL, or [B] device array: sequence b has only its first kv_lens[b] keys (<= Lkv)
+    const int32_t* q_lens;   // NULL, or [B] device array: only the first q_lens[b] query rows of sequence b are computed
+                             //   and written (prefill and fp32 kernels; the decode kernel computes all its <= 16 rows)
     bool causal;  // the Lq queries are the last Lq of the Lkv tokens and see nothing after themselves
     float* O;     // [B,Hq,Lq,D]
     float* lse;   // [B,Hq,Lq]

@@ -146,12 +146,14 @@ def test_local_attn_and_unpermute_lse_validation(lib):
 def test_partial_attn_varlen_validation(lib):
     s = shape()
     f = lib.fedrag_partial_attn_varlen
-    ok_args = lambda: [ctypes.byref(s), 64, 256, P(A), P(2 * A), P(3 * A), P(6 * A), ctypes.c_float(0.1), P(4 * A),
+    ok_args = lambda: [ctypes.byref(s), 64, 256, P(A), P(2 * A), P(3 * A), P(6 * A), None, ctypes.c_float(0.1), P(4 * A),
                        P(5 * A), None, 0, None]
-    for i in (0, 3, 4, 5, 6, 8, 9):
+    for i in (0, 3, 4, 5, 6, 9, 10):
         a = ok_args(); a[i] = None
         assert f(*a) == fb.ERR_NULL
     a = ok_args(); a[6] = P(6 * A + 2)        # misaligned lengths
+    assert f(*a) == fb.ERR_ALIAS
+    a = ok_args(); a[7] = P(7 * A + 1)        # misaligned query lengths
     assert f(*a) == fb.ERR_ALIAS
     a = ok_args(); a[2] = -1
     assert f(*a) == fb.ERR_SHAPE

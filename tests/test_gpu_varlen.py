@@ -41,3 +41,25 @@ def test_partial_attn_varlen(oracle, case):
     torch.cuda.synchronize()
     Or, lr = oracle.partial_attn_varlen(Qs, Ks, Vs, lens_t)
     PT.check_attn(O, lse, Or, lr, dtype, name)
+
+
+@pytest.mark.parametrize("dt,d", [("bf16", 64), ("f32", 64)])
+def test_query_lengths_skip_padding_rows(oracle, dt, d):
+    """Re-ranking pairs: every token of a pair attends to the pair; rows past a pair's length are not written."""
+    dtype = W.torch_dtype(dt)
+    B, H, Lmax = 4, 4, 600
+    lens = [600, 257, 0, 300]
+    seed = 321
+    mk = lambda tid: W.activations(B, H, Lmax, d, seed=seed, tensor_id=tid, outliers=False, dtype=dtype)
+    Q, K, V = mk(W.TID_Q), mk(W.TID_K), mk(W.TID_V)
+    lens_t = torch.tensor(lens, dtype=torch.int32)
+    O = torch.full((B, H, Lmax, d), 7.0, dtype=torch.float32, device=DEV)
+    lse = torch.full((B, H, Lmax), 7.0, dtype=torch.float32, device=DEV)
+    fb.fedrag_partial_attn_varlen(Q.to(DEV), K.to(DEV), V.to(DEV), lens_t.to(DEV), O_part=O, lse=lse,
+                                  q_lens=lens_t.to(DEV))
+    torch.cuda.synchronize()
+    Or, lr = oracle.partial_attn_varlen(Q, K, V, lens_t)
+    for b, n in enumerate(lens):
+        if n:
+            PT.check_attn(O[b:b + 1, :, :n], lse[b:b + 1, :, :n], Or[b:b + 1, :, :n], lr[b:b + 1, :, :n], dtype, f"seq {b}")
+        assert bool((O[b, :, n:] == 7.0).all()) and bool((lse[b, :, n:] == 7.0).all()), "padding rows were written"
