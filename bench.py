@@ -227,6 +227,65 @@ def rerank_leg(torch, W, fb, dev, steps, warmup):
             "value": round(flop / (t["avg_us"] * 1e-6) / 1e12, 1), "unit": "TFLOP/s"}
 
 
+def mixed_leg(torch, W, fb, dev, steps, warmup):
+    """70B-shaped mixed batch (64 query heads over 8 KV heads, 8 shards x 8192 tokens): 32 decoding sequences and one
+    4096-token prefill chunk.  partial_attn over the 8 shards + lse_merge for each part, alone and with the two parts
+    issued on two streams at once (scramble_kv is timed on its own in the main step)."""
+    cd, cp = W.CONFIGS["mixed70b_decode"], W.CONFIGS["mixed70b_prefill"]
+    dt = W.torch_dtype(cd.dtype)
+    S, d = cd.n_shards, cd.d_head
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(cd.seed)
+    rnd = lambda *shape: torch.randn(shape, generator=gen, device=dev).to(dt)
+
+    def part(cfg):
+        Q = rnd(cfg.batch, cfg.n_q_heads, cfg.L_q, d)
+        KV = [(rnd(cfg.batch, cfg.n_kv_heads, cfg.L_kv, d), rnd(cfg.batch, cfg.n_kv_heads, cfg.L_kv, d))
+              for _ in range(S)]
+        O = torch.empty((S, cfg.batch, cfg.n_q_heads, cfg.L_q, d), dtype=torch.float32, device=dev)
+        lse = torch.empty((S, cfg.batch, cfg.n_q_heads, cfg.L_q), dtype=torch.float32, device=dev)
+        Om, lm = torch.empty_like(O[0]), torch.empty_like(lse[0])
+        need = fb.fedrag_partial_attn_workspace_bytes(cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, d, dt, cfg.L_q, cfg.L_kv)
+        ws = torch.empty(max(need, 16), dtype=torch.uint8, device=dev)
+
+        def run():
+            for s_ in range(S):
+                fb.fedrag_partial_attn(Q, KV[s_][0], KV[s_][1], None, O_part=O[s_], lse=lse[s_], workspace=ws)
+            fb.fedrag_lse_merge(O, lse, O_out=Om, lse_out=lm)
+        return run
+
+    run_d, run_p = part(cd), part(cp)
+    s_d, s_p = torch.cuda.Stream(), torch.cuda.Stream()   # default priority, both
+
+    def timed(fn):
+        for _ in range(warmup):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            fn()
+        torch.cuda.synchronize()
+        return 1e3 * (time.perf_counter() - t0) / steps
+
+    def both():
+        with torch.cuda.stream(s_p):
+            run_p()
+        with torch.cuda.stream(s_d):
+            run_d()
+
+    ms_d, ms_p, ms_b = timed(run_d), timed(run_p), timed(both)
+    byts = 4.0 * d * cd.batch * cd.n_kv_heads * cd.L_kv * S              # K' + V', 16-bit, read once per KV head
+    flop = 4.0 * cp.L_q * cp.L_kv * S * d * cp.n_q_heads * cp.batch
+    return {"workload": "mixed70b: Hq64 Hkv8 d128, 8 shards x 8192 tokens, bf16; 32 decode sequences + one 4096-token "
+                        "prefill chunk; partial_attn x 8 + lse_merge per part",
+            "decode": {"ms": round(ms_d, 4), "GB/s": round(byts / ms_d / 1e6, 1),
+                       "frac_hbm": round(byts / ms_d / 1e6 / HBM_PEAK_GBS, 4)},
+            "prefill": {"ms": round(ms_p, 4), "TFLOP/s": round(flop / ms_p / 1e9, 1),
+                        "frac_mfma": round(flop / ms_p / 1e9 / MFMA_BF16_PEAK_TFLOPS, 4)},
+            "both_on_two_streams_ms": round(ms_b, 4), "sum_ms": round(ms_d + ms_p, 4),
+            "max_ms": round(max(ms_d, ms_p), 4)}
+
+
 def codec_leg(torch, fb, g, steps, warmup):
     """Transport codec on one shard's K' ([16, 8, 8192, 128] bf16): quantise to 8 bits and back, bytes = read + write."""
     X = g["Ks"][0]
@@ -435,6 +494,7 @@ def main():
     if not args.no_prefill:
         line["rerank"] = rerank_leg(torch, W, fb, dev, max(5, args.steps // 2), args.warmup)
         line["local_attn"] = local_attn_leg(torch, W, fb, dev, max(5, args.steps // 2), args.warmup)
+        line["mixed70b"] = mixed_leg(torch, W, fb, dev, max(5, args.steps // 2), args.warmup)
         line["prefill"] = prefill_leg(torch, W, fb, dev, max(5, args.steps // 2), args.warmup)
     if not args.no_cpu:
         line["cpu_baseline"] = cpu_leg(torch, W, g, args.cpu_shards)

@@ -48,9 +48,11 @@ __device__ __forceinline__ float structured_entry(float s_in_k, int p_in_inv_k, 
 
 // blockIdx.x = (head * members + member) * b_groups + bg; blockIdx.y selects the job (K or V).
 // The `members` workgroups of one (job, head) share that head's Phi and sweep the sequences b = 0..B-1 together:
-// in every [L, d] slab member m takes the contiguous m-th part of the rows, as 32-row tiles dealt round-robin to
-// its 4 waves.  So at any moment the chip reads and writes a few slabs (one per job and head) rather than one
-// distant region per workgroup, and Phi is staged once per workgroup for all sequences.  (When the slabs are too
+// every [L, d] slab is cut into 128-row groups dealt round-robin to the members, and the 4 waves of a member take
+// the 32-row tiles of its group.  So at any moment the members of a (job, head) write one contiguous window that
+// moves down the slab, the windows of all jobs and heads sit at the same offset inside their slabs (measured: a few
+// per cent faster than one contiguous part per member, and than windows at staggered offsets), and Phi is staged
+// once per workgroup for all sequences.  (When the slabs are too
 // short to occupy the chip that way - decode queries - the sequences are dealt to b_groups workgroups instead.)
 // A ring of NBUF register tile sets keeps NBUF-1 gathered tiles (8 KiB each) in flight per wave behind the LDS
 // staging and the MFMAs (it runs straight through the slab boundaries); the gather indices of a tile are fetched
@@ -147,7 +149,7 @@ __global__ __launch_bounds__(kScrThreads, 1) void scramble_rows_kernel(ScrambleJ
     auto tile_b = [&](int i) { return bg + (i / tiles_per_slab) * b_groups; };
     auto tile_row0 = [&](int i) {
         const int k = i % tiles_per_slab;
-        return ((int64_t)(member * tiles_per_slab + k) * kScrWaves + wave) * kScrRows;
+        return ((int64_t)(k * members + member) * kScrWaves + wave) * kScrRows;
     };
     auto slab_off = [&](int i) { return ((int64_t)tile_b(i) * H + h) * L * D; };
     const elem* Xj = (const elem*)job.X;
