@@ -286,6 +286,90 @@ def mixed_leg(torch, W, fb, dev, steps, warmup):
             "max_ms": round(max(ms_d, ms_p), 4)}
 
 
+def request_leg(torch, W, fb, dev, steps, warmup, n_layers=32):
+    """The attention path of one request at the largest length configuration of Section 7.1 (context 4096 + 4096 on
+    two Context Owners, 128-token query segment), Llama-3-8B-shaped (32 layers, 32/8 heads of 128), batch 1:
+    per layer scramble_q -> partial_attn on the two shards -> lse_merge -> unscramble, the Inquirer's own causal
+    attention, and the 2-way merge of the two.  Once for the 128-token segment (prefill) and once for one decoded
+    token (the segment's 128 + 64 generated tokens local), each as one HIP graph of all layers."""
+    B, Hq, Hkv, d, S, Lc, Lseg, Lgen = 1, 32, 8, 128, 2, 4096, 128, 64
+    dt = torch.bfloat16
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(W.BASE_SEED + 9)
+    rnd = lambda *shape: torch.randn(shape, generator=gen, device=dev).to(dt)
+    keys = W.make_keys(Hkv, d, Lseg, Lc, S, seed=W.BASE_SEED + 9, dtype=dt)
+    phi_q, phi_vi = keys.phi_q.to(dev), keys.phi_v_inv.to(dev)
+    # per layer: the scrambled caches the Compute Node holds (distinct memory per layer, 1 GiB in all)
+    Ks = [[rnd(B, Hkv, Lc, d) for _ in range(S)] for _ in range(n_layers)]
+    Vs = [[rnd(B, Hkv, Lc, d) for _ in range(S)] for _ in range(n_layers)]
+
+    def chain(Lq, L_local):
+        Q = rnd(B, Hq, Lq, d)
+        Kl = [rnd(B, Hkv, L_local, d) for _ in range(n_layers)]   # the Inquirer's own plaintext K, V per layer
+        Vl = [rnd(B, Hkv, L_local, d) for _ in range(n_layers)]
+        perm_q = keys.perm_q.to(dev) if Lq == Lseg else None
+        f32 = lambda *shape: torch.empty(shape, dtype=torch.float32, device=dev)
+        Qs = torch.empty_like(Q)
+        Op, lp = f32(S, B, Hq, Lq, d), f32(S, B, Hq, Lq)
+        Om, lm, Ou, lu = f32(B, Hq, Lq, d), f32(B, Hq, Lq), f32(B, Hq, Lq, d), f32(B, Hq, Lq)
+        pair_O, pair_l = f32(2, B, Hq, Lq, d), f32(2, B, Hq, Lq)
+        out, out_l = f32(B, Hq, Lq, d), f32(B, Hq, Lq)
+        need = fb.fedrag_partial_attn_workspace_bytes(B, Hq, Hkv, d, dt, Lq, Lc)
+        ws = torch.empty(max(need, 16), dtype=torch.uint8, device=dev)
+        need_l = fb.fedrag_partial_attn_workspace_bytes(B, Hq, Hkv, d, dt, Lq, L_local)
+        ws_l = torch.empty(max(need_l, 16), dtype=torch.uint8, device=dev)
+
+        def layer(i):
+            fb.fedrag_scramble_q(Q, phi_q, perm_q, Q_out=Qs)
+            for s_ in range(S):
+                fb.fedrag_partial_attn(Qs, Ks[i][s_], Vs[i][s_], None, O_part=Op[s_], lse=lp[s_], workspace=ws)
+            fb.fedrag_lse_merge(Op, lp, n_kv_heads=Hkv, O_out=Om, lse_out=lm)
+            fb.fedrag_unscramble(Om, phi_vi, perm_q, O_out=pair_O[0])
+            fb.fedrag_unpermute_lse(lm, perm_q, lse_out=pair_l[0])
+            fb.fedrag_local_attn(Q, Kl[i], Vl[i], None, O_part=pair_O[1], lse=pair_l[1], workspace=ws_l)
+            fb.fedrag_lse_merge(pair_O, pair_l, n_kv_heads=Hkv, O_out=out, lse_out=out_l)
+
+        def all_layers():
+            for i in range(n_layers):
+                layer(i)
+        return all_layers, out
+
+    res = {"workload": "request: B1 Hq32 Hkv8 d128 bf16, 32 layers, context 4096 + 4096 on 2 shards, 128-token query "
+                       "segment; 8 C-ABI calls per layer"}
+    for name, Lq, L_local in (("segment_prefill", Lseg, Lseg), ("decode_token", 1, Lseg + Lgen)):
+        run, out = chain(Lq, L_local)
+        for _ in range(max(1, warmup)):
+            run()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            run()
+        torch.cuda.synchronize()
+        eager_ms = 1e3 * (time.perf_counter() - t0) / steps
+        ref = out.clone()
+        graph = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                run()
+        torch.cuda.current_stream().wait_stream(side)
+        out.fill_(0.0)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        same = bool(torch.equal(out, ref))
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        graph_ms = 1e3 * (time.perf_counter() - t0) / steps
+        res[name] = {"eager_ms": round(eager_ms, 4), "graph_ms": round(graph_ms, 4),
+                     "graph_us_per_layer": round(1e3 * graph_ms / n_layers, 2), "replay_equals_eager": same}
+    res["decode_token"]["tokens_per_s_attention_path"] = round(1e3 / res["decode_token"]["graph_ms"], 1)
+    return res
+
+
 def codec_leg(torch, fb, g, steps, warmup):
     """Transport codec on one shard's K' ([16, 8, 8192, 128] bf16): quantise to 8 bits and back, bytes = read + write."""
     X = g["Ks"][0]
@@ -494,6 +578,7 @@ def main():
     if not args.no_prefill:
         line["rerank"] = rerank_leg(torch, W, fb, dev, max(5, args.steps // 2), args.warmup)
         line["local_attn"] = local_attn_leg(torch, W, fb, dev, max(5, args.steps // 2), args.warmup)
+        line["request"] = request_leg(torch, W, fb, dev, max(5, args.steps // 2), args.warmup)
         line["mixed70b"] = mixed_leg(torch, W, fb, dev, max(5, args.steps // 2), args.warmup)
         line["prefill"] = prefill_leg(torch, W, fb, dev, max(5, args.steps // 2), args.warmup)
     if not args.no_cpu:

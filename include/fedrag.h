@@ -104,6 +104,30 @@ fedrag_status fedrag_partial_attn(const fedrag_shape* shape, int64_t L_q, int64_
 size_t fedrag_partial_attn_workspace_bytes(const fedrag_shape* shape, int64_t L_q, int64_t L_kv);
 
 /*
+ * Section 4.1 as a whole on a Compute Node that holds the shards of several Context Owners for the same queries:
+ * the per-shard computation of fedrag_partial_attn on each of the n_shards shards and the aggregation of
+ * fedrag_lse_merge over them, in one call (one attention launch over all shards' keys plus one aggregation launch,
+ * instead of one of each per shard - what counts when a shard is a few thousand tokens and a launch costs as much
+ * as its work).  The result equals attention over the concatenation of the shards' keys (eq. (1)).
+ * n_shards : 1 .. FEDRAG_MAX_SHARDS.  L_kv, Ks, Vs : HOST arrays of n_shards entries - shard lengths (>= 0; an empty
+ * shard contributes nothing and its pointers may be NULL) and DEVICE pointers to [B,Hkv,L_kv[i],d] tensors in
+ * shape->dtype (16-byte aligned).  The arrays are read during the call only.
+ * Qs as in fedrag_partial_attn.  O : fp32 [B,Hq,L_q,d], lse : fp32 [B,Hq,L_q], aggregated over all shards; all
+ * shards empty gives O = 0, lse = -inf.
+ * workspace : at least fedrag_partial_attn_shards_workspace_bytes(shape, L_q, n_shards, L_kv) bytes of device
+ * scratch (that function returns 0 for arguments this call would reject); may be NULL only when that is 0.
+ * Errors as fedrag_partial_attn; n_shards out of range is FEDRAG_ERR_SHAPE.
+ */
+#define FEDRAG_MAX_SHARDS 16
+fedrag_status fedrag_partial_attn_shards(const fedrag_shape* shape, int64_t L_q, int32_t n_shards,
+                                         const int64_t* L_kv, const void* const* Ks, const void* const* Vs,
+                                         const void* Qs, float softmax_scale, float* O, float* lse,
+                                         void* workspace, size_t workspace_bytes, void* stream);
+
+size_t fedrag_partial_attn_shards_workspace_bytes(const fedrag_shape* shape, int64_t L_q, int32_t n_shards,
+                                                  const int64_t* L_kv);
+
+/*
  * fedrag_partial_attn over a batch of sequences of unequal length stored padded to L_kv rows (Section 5.2: the
  * re-ranker scores several query-document pairs at once, each a sequence of its own): sequence b attends to its
  * first kv_lens[b] keys only; rows of Ks, Vs past that are never used in the result and may hold anything.

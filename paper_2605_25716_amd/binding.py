@@ -19,7 +19,8 @@ F32, BF16, F16 = 0, 1, 2
 _DTYPES = {torch.float32: F32, torch.bfloat16: BF16, torch.float16: F16}
 
 EXPORTS = ("fedrag_scramble_kv", "fedrag_scramble_q", "fedrag_partial_attn",
-           "fedrag_partial_attn_workspace_bytes", "fedrag_lse_merge", "fedrag_unscramble",
+           "fedrag_partial_attn_workspace_bytes", "fedrag_partial_attn_shards",
+           "fedrag_partial_attn_shards_workspace_bytes", "fedrag_lse_merge", "fedrag_unscramble",
            "fedrag_scramble_kv_structured", "fedrag_scramble_q_structured", "fedrag_unscramble_structured",
            "fedrag_local_attn", "fedrag_unpermute_lse", "fedrag_partial_attn_varlen", "fedrag_quantize_rows",
            "fedrag_dequantize_rows", "fedrag_scramble_kv_quantized", "fedrag_scramble_kv_structured_quantized",
@@ -67,6 +68,12 @@ def load() -> ctypes.CDLL:
         lib.fedrag_partial_attn.argtypes = [sp, i64, i64, vp, vp, vp, ctypes.c_float, f32p, f32p, vp,
                                             ctypes.c_size_t, vp]
         lib.fedrag_local_attn.argtypes = lib.fedrag_partial_attn.argtypes
+        lib.fedrag_partial_attn_shards.argtypes = [sp, i64, ctypes.c_int32, ctypes.POINTER(ctypes.c_int64),
+                                                   ctypes.POINTER(ctypes.c_void_p), ctypes.POINTER(ctypes.c_void_p),
+                                                   vp, ctypes.c_float, f32p, f32p, vp, ctypes.c_size_t, vp]
+        lib.fedrag_partial_attn_shards_workspace_bytes.argtypes = [sp, i64, ctypes.c_int32,
+                                                                   ctypes.POINTER(ctypes.c_int64)]
+        lib.fedrag_partial_attn_shards_workspace_bytes.restype = ctypes.c_size_t
         lib.fedrag_partial_attn_varlen.argtypes = [sp, i64, i64, vp, vp, vp, vp, vp, ctypes.c_float, f32p, f32p, vp,
                                                    ctypes.c_size_t, vp]
         lib.fedrag_unpermute_lse.argtypes = [sp, i64, f32p, vp, f32p, vp]
@@ -186,6 +193,32 @@ def fedrag_partial_attn(Qs, Ks, Vs, softmax_scale: Optional[float] = None, O_par
                                     _ptr(lse), _ptr(workspace), ws_bytes, _stream())
     _check(st, "fedrag_partial_attn")
     return O_part, lse
+
+
+def fedrag_partial_attn_shards(Qs, Ks_list, Vs_list, softmax_scale: Optional[float] = None, O=None, lse=None,
+                               workspace=None):
+    """Per-shard attention and its aggregation over the shards in one call.  Qs [B,Hq,Lq,d];
+    Ks_list[i], Vs_list[i] [B,Hkv,L_i,d] -> fp32 [B,Hq,Lq,d], fp32 [B,Hq,Lq] over all shards' keys."""
+    B, Hq, Lq, d = Qs.shape
+    n = len(Ks_list)
+    Hkv = Ks_list[0].shape[1]
+    shape = make_shape(B, Hq, Hkv, d, Qs.dtype)
+    if softmax_scale is None:
+        softmax_scale = float(d) ** -0.5
+    O = torch.empty((B, Hq, Lq, d), dtype=torch.float32, device=Qs.device) if O is None else O
+    lse = torch.empty((B, Hq, Lq), dtype=torch.float32, device=Qs.device) if lse is None else lse
+    Ls = (ctypes.c_int64 * n)(*[int(k.shape[2]) for k in Ks_list])
+    Kp = (ctypes.c_void_p * n)(*[_ptr(k) if k.shape[2] > 0 else None for k in Ks_list])
+    Vp = (ctypes.c_void_p * n)(*[_ptr(v) if v.shape[2] > 0 else None for v in Vs_list])
+    need = int(load().fedrag_partial_attn_shards_workspace_bytes(ctypes.byref(shape), Lq, n, Ls))
+    if workspace is None and need > 0:
+        workspace = torch.empty(need, dtype=torch.uint8, device=Qs.device)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    st = load().fedrag_partial_attn_shards(ctypes.byref(shape), Lq, n, Ls, Kp, Vp, _ptr(Qs),
+                                           ctypes.c_float(softmax_scale), _ptr(O), _ptr(lse), _ptr(workspace),
+                                           ws_bytes, _stream())
+    _check(st, "fedrag_partial_attn_shards")
+    return O, lse
 
 
 def fedrag_partial_attn_varlen(Qs, Ks, Vs, kv_lens, softmax_scale: Optional[float] = None, O_part=None, lse=None,

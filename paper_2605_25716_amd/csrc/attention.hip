@@ -8,6 +8,9 @@
 #include "fedrag_device.h"
 #include "fedrag_host.h"
 
+#include <climits>
+#include <cstdint>
+
 namespace fedrag {
 
 // ------------------------------------------------------------------------------------------------ fp32 path
@@ -113,33 +116,89 @@ static int decode_target_wgs() {
 #endif
 static bool use_decode_kernel(int Hq, int Hkv, int64_t Lq) { return (int64_t)(Hq / Hkv) * Lq <= 16; }
 
-int attn_kv_splits(int B, int Hq, int Hkv, int D, int dtype, int64_t Lq, int64_t Lkv) {
-    (void)D;
-    if (dtype == FEDRAG_F32 || Lkv <= 0 || Lq <= 0 || !use_decode_kernel(Hq, Hkv, Lq)) return 1;
-    const int64_t units = (int64_t)B * Hkv;
-    if (units <= 0) return 1;
-    // a split is a whole number of 128-key workgroup steps
-    int64_t want = (FEDRAG_DEC_WGS + units - 1) / units;
-    if (want < 1) want = 1;
-    int64_t per = (Lkv + want - 1) / want;
-    per = ((per + kDecStride - 1) / kDecStride) * kDecStride;
-    if (per < 4 * kDecStride) per = 4 * kDecStride;
-    if (per > (int64_t)1 << 22) per = (int64_t)1 << 22;  // a split stays below 2^31 bytes (32-bit buffer offsets)
-    return (int)((Lkv + per - 1) / per);
+// Decode kernel: about one workgroup per compute unit over the whole launch; a run is a whole number of 128-key
+// workgroup steps, at least 4 of them, and stays below 2^31 bytes (32-bit buffer offsets).
+// Prefill kernel: one workgroup per (sequence, query head, 256 query rows) walks a run, about 2 us per 64-key tile.
+// When those workgroups cover less than half of the compute units, the keys are cut into runs of at least
+// kPreMinTilesPerSplit tiles (so that a workgroup's fixed cost stays small beside its tiles) for one round of
+// workgroups over the chip; otherwise every shard is one run.
+KeyRuns attn_plan_runs(int B, int Hq, int Hkv, int dtype, int64_t Lq, int n, const int64_t* Ls) {
+    KeyRuns r;
+    for (int i = 0; i < kMaxShards; ++i) {
+        r.K[i] = r.V[i] = nullptr;
+        r.L[i] = 0;
+        r.per[i] = 1;
+        r.first[i] = INT_MAX;
+    }
+    r.first[kMaxShards] = INT_MAX;
+    r.n_runs = 0;
+    if (n < 1 || n > kMaxShards) return r;
+    int64_t total = 0;
+    for (int i = 0; i < n; ++i) total += Ls[i] > 0 ? Ls[i] : 0;
+    const bool decode = use_decode_kernel(Hq, Hkv, Lq);
+    const int64_t cus = FEDRAG_DEC_WGS;
+    int64_t per = INT64_MAX;  // keys per run before rebalancing inside a shard
+    int64_t quantum = 1;
+    if (dtype != FEDRAG_F32 && total > 0 && Lq > 0) {
+        if (decode) {
+            const int64_t units = (int64_t)B * Hkv;
+            const int64_t want = units > 0 ? (cus + units - 1) / units : 1;
+            quantum = kDecStride;
+            per = (total + want - 1) / want;
+            per = ((per + quantum - 1) / quantum) * quantum;
+            if (per < 4 * quantum) per = 4 * quantum;
+            if (per > (int64_t)1 << 22) per = (int64_t)1 << 22;
+        } else {
+            const int64_t wgs = (int64_t)B * Hq * ((Lq + kPreQTile - 1) / kPreQTile);
+            quantum = kPreK;
+            if (wgs > 0 && wgs * 2 <= cus) {
+                const int64_t want = cus / wgs;
+                const int64_t tiles = (total + kPreK - 1) / kPreK;
+                int64_t per_t = (tiles + want - 1) / want;
+                if (per_t < kPreMinTilesPerSplit) per_t = kPreMinTilesPerSplit;
+                per = per_t * kPreK;
+            }
+        }
+    }
+    int at = 0;
+    for (int i = 0; i < n; ++i) {
+        const int64_t L = Ls[i] > 0 ? Ls[i] : 0;
+        r.L[i] = L;
+        r.first[i] = at;
+        if (L == 0) continue;  // no runs: first[i] == first[i + 1]
+        const int64_t runs = per == INT64_MAX ? 1 : (L + per - 1) / per;
+        int64_t mine = (L + runs - 1) / runs;  // rebalanced inside the shard
+        mine = ((mine + quantum - 1) / quantum) * quantum;
+        r.per[i] = mine;
+        at += (int)((L + mine - 1) / mine);
+    }
+    for (int i = n; i <= kMaxShards; ++i) r.first[i] = i == n ? at : INT_MAX;
+    r.n_runs = at;
+    return r;
+}
+
+KeyRuns attn_runs_of(const AttnProblem& p) {
+    if (p.n_shards <= 1) {
+        KeyRuns r = attn_plan_runs(p.B, p.Hq, p.Hkv, p.dtype, p.Lq, 1, &p.Lkv);
+        r.K[0] = p.K;
+        r.V[0] = p.V;
+        return r;
+    }
+    KeyRuns r = attn_plan_runs(p.B, p.Hq, p.Hkv, p.dtype, p.Lq, p.n_shards, p.Ls);
+    for (int i = 0; i < p.n_shards && i < kMaxShards; ++i) {
+        r.K[i] = p.Ks[i];
+        r.V[i] = p.Vs[i];
+    }
+    return r;
 }
 
 bool attn_uses_decode_kernel(int Hq, int Hkv, int64_t Lq) { return use_decode_kernel(Hq, Hkv, Lq); }
 
-int64_t decode_keys_per_split(int64_t Lkv, int n_splits) {
-    int64_t per = (Lkv + n_splits - 1) / n_splits;
-    return ((per + kDecStride - 1) / kDecStride) * kDecStride;
-}
-
-size_t attn_workspace_bytes(int B, int Hq, int Hkv, int D, int dtype, int64_t Lq, int64_t Lkv) {
-    const int s = attn_kv_splits(B, Hq, Hkv, D, dtype, Lq, Lkv);
-    if (s <= 1) return 0;
+size_t attn_workspace_bytes(int B, int Hq, int Hkv, int D, int dtype, int64_t Lq, int n, const int64_t* Ls) {
+    const KeyRuns r = attn_plan_runs(B, Hq, Hkv, dtype, Lq, n, Ls);
+    if (r.n_runs <= 1) return 0;
     const size_t rows = (size_t)B * Hq * (size_t)Lq;
-    return (size_t)s * rows * (size_t)(D + 1) * sizeof(float);
+    return (size_t)r.n_runs * rows * (size_t)(D + 1) * sizeof(float);
 }
 
 template <int D>
@@ -156,6 +215,37 @@ hipError_t launch_partial_attn(const AttnProblem& p_in, hipStream_t stream) {
     if (p.Lq == 1) p.causal = false;  // a single query at the last position sees every key
     const int64_t rows = (int64_t)p.B * p.Hq * p.Lq;
     if (rows == 0) return hipSuccess;
+    if (p.n_shards > 1) {
+        if (p.n_shards > kMaxShards || p.quant_bits != 0 || p.causal || p.kv_lens || p.q_lens) return hipErrorInvalidValue;
+        int64_t total = 0;
+        for (int i = 0; i < p.n_shards; ++i) total += p.Ls[i];
+        if (total == 0) return launch_fill_empty(p.O, p.lse, rows, p.D, stream);
+        if (p.dtype == FEDRAG_F32) {
+            // accuracy path: one launch per non-empty shard into the workspace ([n][rows][D] then [n][rows]),
+            // then the aggregation
+            int idx[kMaxShards], n = 0;
+            for (int i = 0; i < p.n_shards; ++i)
+                if (p.Ls[i] > 0) idx[n++] = i;
+            if (n > 1 && (!p.workspace || p.workspace_bytes < (size_t)n * rows * (p.D + 1) * sizeof(float)))
+                return hipErrorInvalidValue;
+            float* Ow = n > 1 ? (float*)p.workspace : p.O;
+            float* Lw = n > 1 ? Ow + (size_t)n * rows * p.D : p.lse;
+            for (int j = 0; j < n; ++j) {
+                AttnProblem one = p;
+                one.n_shards = 1;
+                one.K = p.Ks[idx[j]];
+                one.V = p.Vs[idx[j]];
+                one.Lkv = p.Ls[idx[j]];
+                one.O = Ow + (size_t)j * rows * p.D;
+                one.lse = Lw + (size_t)j * rows;
+                const hipError_t e = launch_partial_attn(one, stream);
+                if (e != hipSuccess) return e;
+            }
+            return n > 1 ? launch_lse_merge(Ow, Lw, n, rows, p.D, p.O, p.lse, stream) : hipSuccess;
+        }
+        if (p.dtype != FEDRAG_BF16 && p.dtype != FEDRAG_F16) return hipErrorInvalidValue;
+        return use_decode_kernel(p.Hq, p.Hkv, p.Lq) ? launch_decode_attn(p, stream) : launch_prefill_attn(p, stream);
+    }
     if (p.Lkv == 0) return launch_fill_empty(p.O, p.lse, rows, p.D, stream);
     if (p.quant_bits != 0) {  // only the decode kernel reads the codec's codes
         if (p.dtype == FEDRAG_F32 || p.causal || p.kv_lens || !use_decode_kernel(p.Hq, p.Hkv, p.Lq))

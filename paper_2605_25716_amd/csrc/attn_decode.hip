@@ -98,11 +98,9 @@ __device__ __forceinline__ typename T::vec8 dequant8(uint32_t w, u32x2_t prm) { 
 
 template <class T, int D, int QB>
 __global__ __launch_bounds__(kDecThreads, FEDRAG_DEC_OCC) void decode_attn_kernel(const typename T::elem* __restrict__ Q,
-                                                                     const void* __restrict__ K,
-                                                                     const void* __restrict__ V,
+                                                                     const KeyRuns runs,
                                                                      const float* __restrict__ Kprm,
                                                                      const float* __restrict__ Vprm, int R,
-                                                                     int64_t L, int n_splits, int64_t keys_per_split,
                                                                      float scale_log2, float* __restrict__ O,
                                                                      float* __restrict__ lse, int64_t total_rows,
                                                                      const int32_t* __restrict__ kv_lens, int Hkv) {
@@ -127,8 +125,24 @@ __global__ __launch_bounds__(kDecThreads, FEDRAG_DEC_OCC) void decode_attn_kerne
     const int lane = tid % kWave;
     const int lr = lane % 16;
     const int lq = lane / 16;
-    const int64_t unit = blockIdx.x / n_splits;
-    const int split = blockIdx.x % n_splits;
+    const int64_t unit = blockIdx.x / runs.n_runs;
+    const int run = blockIdx.x % runs.n_runs;  // index of this workgroup's partial
+    // the shard this run belongs to (scalar compares against the table; first[] is INT_MAX past the last shard)
+    const void* K = runs.K[0];
+    const void* V = runs.V[0];
+    int64_t L = runs.L[0];
+    int64_t keys_per_split = runs.per[0];
+    int split = run;
+#pragma unroll
+    for (int i = 1; i < kMaxShards; ++i) {
+        if (run >= runs.first[i]) {
+            K = runs.K[i];
+            V = runs.V[i];
+            L = runs.L[i];
+            keys_per_split = runs.per[i];
+            split = run - runs.first[i];
+        }
+    }
     const int64_t k_begin = (int64_t)split * keys_per_split;
     // keys of this unit's sequence: all L rows, or the first kv_lens[b] of them (padded batch of unequal sequences);
     // a split that starts past them is empty and returns O = 0, lse = -inf like an empty shard
@@ -361,8 +375,8 @@ __global__ __launch_bounds__(kDecThreads, FEDRAG_DEC_OCC) void decode_attn_kerne
             for (int r = 0; r < 4; ++r) sm_o[wave][lr][DCH * (4 * lq + r) + i] = acc_o[i][r];
     }
     __syncthreads();
-    float* Oout = O + ((int64_t)split * total_rows + unit * R) * D;
-    float* Lout = lse + (int64_t)split * total_rows + unit * R;
+    float* Oout = O + ((int64_t)run * total_rows + unit * R) * D;
+    float* Lout = lse + (int64_t)run * total_rows + unit * R;
     for (int idx = tid; idx < R * D; idx += kDecThreads) {
         const int n = idx / D;
         const int d = idx % D;
@@ -387,19 +401,22 @@ static hipError_t launch_decode_t(const AttnProblem& p, hipStream_t stream) {
     typedef typename T::elem elem;
     const float scale_log2 = p.scale * kLog2e;
     const int64_t rows = (int64_t)p.B * p.Hq * p.Lq;
-    const int splits = attn_kv_splits(p.B, p.Hq, p.Hkv, D, p.dtype, p.Lq, p.Lkv);
-    const int64_t per = decode_keys_per_split(p.Lkv, splits);
+    const KeyRuns runs = attn_runs_of(p);
+    const int splits = runs.n_runs;
+    if (splits < 1) return hipErrorInvalidValue;
+    if (QB != 0 && p.n_shards > 1) return hipErrorInvalidValue;
     const int R = (int)((p.Hq / p.Hkv) * p.Lq);
     const int64_t units = (int64_t)p.B * p.Hkv;
     float* Odst = p.O;
     float* Ldst = p.lse;
     if (splits > 1) {
+        if (!p.workspace || p.workspace_bytes < (size_t)splits * rows * (D + 1) * sizeof(float)) return hipErrorInvalidValue;
         Odst = (float*)p.workspace;
         Ldst = Odst + (size_t)splits * rows * D;
     }
     hipLaunchKernelGGL((decode_attn_kernel<T, D, QB>), dim3((unsigned)(units * splits)), dim3(kDecThreads), 0, stream,
-                       (const elem*)p.Q, p.K, p.V, p.K_params, p.V_params, R, p.Lkv, splits, per, scale_log2, Odst, Ldst,
-                       rows, p.kv_lens, p.Hkv);
+                       (const elem*)p.Q, runs, p.K_params, p.V_params, R, scale_log2, Odst, Ldst, rows, p.kv_lens,
+                       p.Hkv);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || splits == 1) return e;
     return launch_lse_merge(Odst, Ldst, splits, rows, D, p.O, p.lse, stream);

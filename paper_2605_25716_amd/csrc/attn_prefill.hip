@@ -20,11 +20,7 @@
 
 namespace fedrag {
 
-constexpr int kPreWaves = 8;
 constexpr int kPreThreads = kPreWaves * kWave;
-constexpr int kPreQ = 32;                     // query rows per wave (one 32-wide MFMA column tile)
-constexpr int kPreQTile = kPreWaves * kPreQ;  // query rows per workgroup
-constexpr int kPreK = 64;                     // keys per LDS tile
 #ifndef FEDRAG_PRE_PD
 #define FEDRAG_PRE_PD 4
 #endif
@@ -44,9 +40,7 @@ __device__ __forceinline__ u32x2_t lds_read_tr16(const char* p) {
 // (Section 5.3: the Inquirer's own part of a decoder layer's attention).
 template <class T, int D, bool CAUSAL>
 __global__ __launch_bounds__(kPreThreads, 1) void prefill_attn_kernel(const typename T::elem* __restrict__ Q,
-                                                                      const typename T::elem* __restrict__ K,
-                                                                      const typename T::elem* __restrict__ V, int Hq,
-                                                                      int Hkv, int64_t Lq, int64_t L_stride,
+                                                                      const KeyRuns runs, int Hq, int Hkv, int64_t Lq,
                                                                       const int32_t* __restrict__ kv_lens,
                                                                       const int32_t* __restrict__ q_lens, int q_tiles,
                                                                       int n_units, float scale_log2,
@@ -66,13 +60,33 @@ __global__ __launch_bounds__(kPreThreads, 1) void prefill_attn_kernel(const type
 
     // XCD-aware placement: consecutive workgroup ids are dealt round-robin to the 8 XCDs (one L2 each);
     // give every XCD whole (sequence, KV head) units so that the workgroups sharing K'/V' share an L2.
+    // With more than one run (several shards, or few query tiles and many keys; not CAUSAL) there is one workgroup
+    // per (query tile, run) and O / lse are [n_runs][rows] partials that the Section 4.1 aggregation folds afterwards.
     const int G = Hq / Hkv;
-    const int per_unit = G * q_tiles;
+    const int n_runs = runs.n_runs;
+    const int per_unit = G * q_tiles * n_runs;
     const int xcd = blockIdx.x % 8;
     const int slot = blockIdx.x / 8;
     const int unit = xcd + 8 * (slot / per_unit);
     if (unit >= n_units) return;
-    const int w_in_unit = slot % per_unit;
+    const int run = (slot % per_unit) % n_runs;
+    const int w_in_unit = (slot % per_unit) / n_runs;
+    // the shard this run belongs to (scalar compares against the table; first[] is INT_MAX past the last shard)
+    const elem* K = (const elem*)runs.K[0];
+    const elem* V = (const elem*)runs.V[0];
+    int64_t L_stride = runs.L[0];
+    int64_t keys_per_run = runs.per[0];
+    int split = run;
+#pragma unroll
+    for (int i = 1; i < kMaxShards; ++i) {
+        if (run >= runs.first[i]) {
+            K = (const elem*)runs.K[i];
+            V = (const elem*)runs.V[i];
+            L_stride = runs.L[i];
+            keys_per_run = runs.per[i];
+            split = run - runs.first[i];
+        }
+    }
     // CAUSAL: later query tiles visit more keys.  Hand out the last tile of every head of the group first, then the
     // one before it, and so on: workgroups are started in index order as compute units free up, so every compute
     // unit ends up with a long tile followed by short ones and the launch does not wait on a late long tile.
@@ -104,8 +118,16 @@ __global__ __launch_bounds__(kPreThreads, 1) void prefill_attn_kernel(const type
         Lq_rows = v < 0 ? 0 : (v < Lq ? v : Lq);
     }
     if ((int64_t)qt * kPreQTile >= Lq_rows) return;  // workgroup-uniform, before any barrier
-    float* Oh = O + ((int64_t)b * Hq + h) * Lq * D;
-    float* Lh = lse + ((int64_t)b * Hq + h) * Lq;
+    const int64_t part_row0 = (int64_t)run * n_units * G * Lq;  // n_units * G * Lq = rows of one partial
+    float* Oh = O + (part_row0 + ((int64_t)b * Hq + h) * Lq) * D;
+    float* Lh = lse + part_row0 + ((int64_t)b * Hq + h) * Lq;
+    if (!CAUSAL && n_runs > 1) {  // this workgroup's run of keys; a run past the end is empty
+        const int64_t k_begin = (int64_t)split * keys_per_run;
+        const int64_t k_end = k_begin + keys_per_run < L ? k_begin + keys_per_run : L;
+        L = k_end > k_begin ? k_end - k_begin : 0;
+        Kg += k_begin * ROWB;
+        Vg += k_begin * ROWB;
+    }
 
     const int64_t q_row = (int64_t)qt * kPreQTile + wave * kPreQ + li;  // this lane's query row
     if (L == 0) {  // no keys (workgroup-uniform, before any barrier): O = 0, lse = -inf
@@ -402,12 +424,33 @@ static hipError_t launch_prefill_t(const AttnProblem& p, hipStream_t stream) {
     const float scale_log2 = p.scale * kLog2e;
     const int q_tiles = (int)((p.Lq + kPreQTile - 1) / kPreQTile);
     const int n_units = p.B * p.Hkv;
-    const int per_unit = (p.Hq / p.Hkv) * q_tiles;
+    // several runs: only the plain call (every key of every sequence, every query row, no mask) takes them
+    KeyRuns runs = attn_runs_of(p);
+    const bool one_run_only = CAUSAL || p.kv_lens || p.q_lens;
+    if (one_run_only) {
+        if (p.n_shards > 1) return hipErrorInvalidValue;
+        runs.per[0] = runs.L[0] > 0 ? ((runs.L[0] + kPreK - 1) / kPreK) * kPreK : kPreK;
+        runs.first[1] = 1;
+        runs.n_runs = 1;
+    }
+    const int splits = runs.n_runs;
+    if (splits < 1) return hipErrorInvalidValue;
+    const int64_t rows = (int64_t)p.B * p.Hq * p.Lq;
+    float* Odst = p.O;
+    float* Ldst = p.lse;
+    if (splits > 1) {
+        if (!p.workspace || p.workspace_bytes < (size_t)splits * rows * (D + 1) * sizeof(float)) return hipErrorInvalidValue;
+        Odst = (float*)p.workspace;
+        Ldst = Odst + (size_t)splits * rows * D;
+    }
+    const int per_unit = (p.Hq / p.Hkv) * q_tiles * splits;
     const int64_t grid = (int64_t)8 * ((n_units + 7) / 8) * per_unit;
-    hipLaunchKernelGGL((prefill_attn_kernel<T, D, CAUSAL>), dim3((unsigned)grid), dim3(kPreThreads), 0,
-                       stream, (const elem*)p.Q, (const elem*)p.K, (const elem*)p.V, p.Hq, p.Hkv, p.Lq, p.Lkv, p.kv_lens, p.q_lens, q_tiles,
-                       n_units, scale_log2, p.O, p.lse);
-    return hipGetLastError();
+    hipLaunchKernelGGL((prefill_attn_kernel<T, D, CAUSAL>), dim3((unsigned)grid), dim3(kPreThreads), 0, stream,
+                       (const elem*)p.Q, runs, p.Hq, p.Hkv, p.Lq, p.kv_lens, p.q_lens, q_tiles, n_units, scale_log2,
+                       Odst, Ldst);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess || splits == 1) return e;
+    return launch_lse_merge(Odst, Ldst, splits, rows, D, p.O, p.lse, stream);
 }
 
 template <class T>

@@ -157,6 +157,55 @@ fedrag_status fedrag_partial_attn(const fedrag_shape* shape, int64_t L_q, int64_
     return dev(launch_partial_attn(p, (hipStream_t)stream));
 }
 
+size_t fedrag_partial_attn_shards_workspace_bytes(const fedrag_shape* shape, int64_t L_q, int32_t n_shards,
+                                                  const int64_t* L_kv) {
+    if (check_shape(shape, true) != FEDRAG_OK || L_q < 0 || n_shards < 1 || n_shards > kMaxShards || !L_kv) return 0;
+    for (int i = 0; i < n_shards; ++i)
+        if (L_kv[i] < 0 || L_kv[i] > INT32_MAX) return 0;
+    return attn_workspace_bytes(shape->batch, shape->n_q_heads, shape->n_kv_heads, shape->d_head, shape->dtype, L_q,
+                                n_shards, L_kv);
+}
+
+fedrag_status fedrag_partial_attn_shards(const fedrag_shape* shape, int64_t L_q, int32_t n_shards, const int64_t* L_kv,
+                                         const void* const* Ks, const void* const* Vs, const void* Qs,
+                                         float softmax_scale, float* O, float* lse, void* workspace,
+                                         size_t workspace_bytes, void* stream) {
+    fedrag_status st = check_shape(shape, true);
+    if (st != FEDRAG_OK) return st;
+    if (n_shards < 1 || n_shards > kMaxShards) return FEDRAG_ERR_SHAPE;
+    if (!L_kv || !Ks || !Vs || !Qs || !O || !lse) return FEDRAG_ERR_NULL;
+    if (L_q < 0 || L_q > INT32_MAX) return FEDRAG_ERR_SHAPE;
+    int64_t nq, nk;
+    if (!tensor_elems(shape->batch, shape->n_q_heads, L_q, shape->d_head, &nq)) return FEDRAG_ERR_SHAPE;
+    for (int i = 0; i < n_shards; ++i) {
+        if (L_kv[i] < 0 || L_kv[i] > INT32_MAX) return FEDRAG_ERR_SHAPE;
+        if (!tensor_elems(shape->batch, shape->n_kv_heads, L_kv[i], shape->d_head, &nk)) return FEDRAG_ERR_SHAPE;
+        if (L_kv[i] > 0 && (!Ks[i] || !Vs[i])) return FEDRAG_ERR_NULL;
+        if (!aligned16(Ks[i]) || !aligned16(Vs[i])) return FEDRAG_ERR_ALIAS;
+    }
+    if (!(softmax_scale > 0.0f) || softmax_scale - softmax_scale != 0.0f) return FEDRAG_ERR_SHAPE;  // finite, > 0
+    if (!aligned16(Qs) || !aligned16(O) || (reinterpret_cast<uintptr_t>(lse) & 3u) || !aligned16(workspace))
+        return FEDRAG_ERR_ALIAS;
+    const size_t need = attn_workspace_bytes(shape->batch, shape->n_q_heads, shape->n_kv_heads, shape->d_head,
+                                             shape->dtype, L_q, n_shards, L_kv);
+    if (need > 0 && (!workspace || workspace_bytes < need)) return FEDRAG_ERR_WORKSPACE;
+    AttnProblem p{};
+    p.B = shape->batch; p.Hq = shape->n_q_heads; p.Hkv = shape->n_kv_heads; p.D = shape->d_head;
+    p.dtype = shape->dtype;
+    p.Lq = L_q;
+    p.Q = Qs;
+    p.scale = softmax_scale;
+    p.O = O; p.lse = lse;
+    p.workspace = workspace; p.workspace_bytes = workspace_bytes;
+    if (n_shards == 1) {
+        p.Lkv = L_kv[0]; p.K = Ks[0]; p.V = Vs[0];
+    } else {
+        p.n_shards = n_shards;
+        for (int i = 0; i < n_shards; ++i) { p.Ks[i] = Ks[i]; p.Vs[i] = Vs[i]; p.Ls[i] = L_kv[i]; }
+    }
+    return dev(launch_partial_attn(p, (hipStream_t)stream));
+}
+
 fedrag_status fedrag_partial_attn_varlen(const fedrag_shape* shape, int64_t L_q, int64_t L_kv, const void* Qs,
                                          const void* Ks, const void* Vs, const int32_t* kv_lens,
                                          const int32_t* q_lens, float softmax_scale, float* O_part, float* lse,

@@ -34,7 +34,9 @@ struct RowsJob {
 hipError_t launch_rows_transform(const RowsJob& job, hipStream_t stream);
 hipError_t launch_invert_perm(const int32_t* perm, int64_t L, int32_t* inv, hipStream_t stream);
 
-// Partial attention problem (one KV shard).
+// Partial attention problem: one KV shard (K, V, Lkv), or - n_shards > 1 - the shards a Compute Node holds for
+// the same queries, (Ks[i], Vs[i], Ls[i]), whose partials are aggregated inside the call.
+constexpr int kMaxShards = 16;
 struct AttnProblem {
     int B, Hq, Hkv, D, dtype;
     int64_t Lq, Lkv;
@@ -43,6 +45,10 @@ struct AttnProblem {
     int quant_bits;          // 0, or 8 / 4: K, V hold the transport codec's codes and K_params, V_params their
     const float* K_params;   //   per-row (scale, lo), [B,Hkv,Lkv,2] (decode shapes, 16-bit dtype, D = 128 only)
     const float* V_params;
+    int n_shards;            // 0 or 1: K, V, Lkv above; else Ks, Vs, Ls below (16-bit dtype, no codes, no lengths, no mask)
+    const void* Ks[kMaxShards];
+    const void* Vs[kMaxShards];
+    int64_t Ls[kMaxShards];
     const int32_t* kv_lens;  // NULL, or [B] device array: sequence b has only its first kv_lens[b] keys (<= Lkv)
     const int32_t* q_lens;   // NULL, or [B] device array: only the first q_lens[b] query rows of sequence b are computed
                              //   and written (prefill and fp32 kernels; the decode kernel computes all its <= 16 rows)
@@ -52,10 +58,29 @@ struct AttnProblem {
     void* workspace;
     size_t workspace_bytes;
 };
-// How the launcher will split the shard's keys across workgroups (1 = no workspace needed).
-int attn_kv_splits(int B, int Hq, int Hkv, int D, int dtype, int64_t Lq, int64_t Lkv);
+// How a launch cuts the keys into runs, one workgroup per (unit of queries, run): what both attention kernels
+// receive by value.  Shard i contributes runs first[i] .. first[i+1]-1 of per[i] keys each (the last one shorter);
+// first[i] = INT_MAX past the last shard, so a kernel finds its shard with compares only.  With more than one run
+// the kernels write one normalised partial per run into the workspace, [n_runs][rows][D] then [n_runs][rows], and
+// the Section 4.1 aggregation folds them.
+struct KeyRuns {
+    const void* K[kMaxShards];
+    const void* V[kMaxShards];
+    int64_t L[kMaxShards];
+    int64_t per[kMaxShards];
+    int first[kMaxShards + 1];
+    int n_runs;
+};
+// Plans the runs for n shards of lengths Ls (n >= 1); pointers are left unset.
+KeyRuns attn_plan_runs(int B, int Hq, int Hkv, int dtype, int64_t Lq, int n, const int64_t* Ls);
 bool attn_uses_decode_kernel(int Hq, int Hkv, int64_t Lq);  // G * Lq <= 16: the HBM-bound streaming kernel
-size_t attn_workspace_bytes(int B, int Hq, int Hkv, int D, int dtype, int64_t Lq, int64_t Lkv);
+// bytes of workspace the plan needs (0 when there is a single run)
+size_t attn_workspace_bytes(int B, int Hq, int Hkv, int D, int dtype, int64_t Lq, int n, const int64_t* Ls);
+inline size_t attn_workspace_bytes(int B, int Hq, int Hkv, int D, int dtype, int64_t Lq, int64_t Lkv) {
+    return attn_workspace_bytes(B, Hq, Hkv, D, dtype, Lq, 1, &Lkv);
+}
+// The plan of problem p with its pointers filled in.
+KeyRuns attn_runs_of(const AttnProblem& p);
 hipError_t launch_partial_attn(const AttnProblem& p, hipStream_t stream);
 
 // decode kernel geometry (shared by the split planner and the kernel)
@@ -63,7 +88,12 @@ constexpr int kDecWaves = 4;
 constexpr int kDecThreads = kDecWaves * 64;
 constexpr int kDecTile = 32;                      // keys per wave step
 constexpr int kDecStride = kDecWaves * kDecTile;  // keys per workgroup step
-int64_t decode_keys_per_split(int64_t Lkv, int n_splits);
+// prefill kernel geometry (shared by the split planner and the kernel)
+constexpr int kPreWaves = 8;
+constexpr int kPreQ = 32;                     // query rows per wave (one 32-wide MFMA column tile)
+constexpr int kPreQTile = kPreWaves * kPreQ;  // query rows per workgroup
+constexpr int kPreK = 64;                     // keys per LDS tile
+constexpr int kPreMinTilesPerSplit = 4;       // a KV split is at least this many tiles
 hipError_t launch_decode_attn(const AttnProblem& p, hipStream_t stream);   // 16-bit storage, G * L_q <= 16
 hipError_t launch_prefill_attn(const AttnProblem& p, hipStream_t stream);  // 16-bit storage, any L_q
 

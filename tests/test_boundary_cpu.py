@@ -278,3 +278,61 @@ def test_binding_refuses_cpu_tensors(lib):
     q = torch.zeros(1, 2, 1, 64)
     with pytest.raises(ValueError):
         fb.fedrag_scramble_q(q, torch.zeros(2, 64, 64))
+
+
+def test_workspace_size_of_prefill_shapes(lib):
+    """Few query tiles and many keys: the keys are cut into runs, the workspace holds one fp32 partial per run
+    (256 compute units assumed without a GPU).  Enough query tiles to fill the chip: no workspace."""
+    def need(B, Hq, Hkv, d, Lq, L, dt=fb.BF16):
+        s = fb.make_shape(B, Hq, Hkv, d, dt)
+        return int(lib.fedrag_partial_attn_workspace_bytes(ctypes.byref(s), Lq, L))
+    # 32 workgroups, 64 tiles -> 8 runs of 8 tiles
+    assert need(1, 32, 8, 128, 128, 4096) == 8 * 32 * 128 * (128 + 1) * 4
+    # 4 workgroups, 24 tiles -> runs of at least 4 tiles -> 6 runs
+    assert need(1, 4, 2, 128, 70, 1500) == 6 * 4 * 70 * (128 + 1) * 4
+    # fewer than 8 tiles: one run
+    assert need(1, 4, 2, 128, 70, 256) == 0
+    # the prefill benchmark shape (256 workgroups) and fp32 storage: no runs
+    assert need(1, 32, 8, 128, 2048, 16384) == 0
+    assert need(1, 4, 2, 128, 70, 1500, fb.F32) == 0
+
+
+def test_partial_attn_shards_validation_and_workspace(lib):
+    s = shape(B=1, Hq=32, Hkv=8)
+    n = 2
+    Ls = (ctypes.c_int64 * n)(4096, 4096)
+    Kp = (ctypes.c_void_p * n)(2 * A, 3 * A)
+    Vp = (ctypes.c_void_p * n)(4 * A, 5 * A)
+    need = lib.fedrag_partial_attn_shards_workspace_bytes(ctypes.byref(s), 1, n, Ls)
+    # 8 units, 256 compute units: 32 runs of 256 keys wanted, a run is at least 512 keys: 8 runs per shard
+    assert need == 16 * 32 * (128 + 1) * 4
+    # the same keys as one shard: the same number of runs
+    one = (ctypes.c_int64 * 1)(8192)
+    assert lib.fedrag_partial_attn_shards_workspace_bytes(ctypes.byref(s), 1, 1, one) == \
+        lib.fedrag_partial_attn_workspace_bytes(ctypes.byref(s), 1, 8192) == need
+    f = lib.fedrag_partial_attn_shards
+    base = lambda: [ctypes.byref(s), 1, n, Ls, Kp, Vp, P(A), ctypes.c_float(0.088), P(6 * A), P(7 * A), P(8 * A), need,
+                    None]
+    for i in (3, 4, 5, 6, 8, 9):
+        a = base(); a[i] = None
+        assert f(*a) == fb.ERR_NULL
+    a = base(); a[2] = 0
+    assert f(*a) == fb.ERR_SHAPE
+    a = base(); a[2] = 17
+    assert f(*a) == fb.ERR_SHAPE
+    a = base(); a[11] = need - 1
+    assert f(*a) == fb.ERR_WORKSPACE
+    a = base(); a[10] = None
+    assert f(*a) == fb.ERR_WORKSPACE
+    a = base(); a[3] = (ctypes.c_int64 * n)(4096, -1)
+    assert f(*a) == fb.ERR_SHAPE
+    a = base(); a[4] = (ctypes.c_void_p * n)(2 * A, None)     # a non-empty shard without keys
+    assert f(*a) == fb.ERR_NULL
+    a = base(); a[5] = (ctypes.c_void_p * n)(4 * A, 5 * A + 4)
+    assert f(*a) == fb.ERR_ALIAS
+    for bad_scale in (float("nan"), 0.0):
+        a = base(); a[7] = ctypes.c_float(bad_scale)
+        assert f(*a) == fb.ERR_SHAPE
+    # bad arguments report 0 bytes
+    assert lib.fedrag_partial_attn_shards_workspace_bytes(ctypes.byref(s), 1, 17, Ls) == 0
+    assert lib.fedrag_partial_attn_shards_workspace_bytes(ctypes.byref(s), 1, n, None) == 0

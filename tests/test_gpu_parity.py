@@ -107,6 +107,10 @@ ATTN_CASES = [
     ("pre_bf16_small", 2, 2, 1, 128, 17, 64, "bf16"),
     ("pre_bf16_d64", 1, 2, 2, 64, 130, 130, "bf16"),
     ("pre_f16", 1, 2, 1, 128, 40, 100, "f16"),
+    # few query tiles, many keys: the keys are cut into runs over more workgroups and the partials merged
+    ("pre_bf16_kv_runs", 1, 4, 2, 128, 70, 1500, "bf16"),       # 24 tiles -> 6 runs of 4, last tile ragged
+    ("pre_bf16_d64_kv_runs", 2, 2, 2, 64, 300, 1111, "bf16"),   # 18 tiles -> runs of 4,4,4,4,2; 2 query tiles
+    ("pre_f16_kv_runs", 1, 2, 1, 128, 40, 777, "f16"),
 ]
 
 
