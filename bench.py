@@ -151,6 +151,30 @@ def graph_leg(torch, fb, g, steps):
     return 1e3 * (time.perf_counter() - t0) / steps
 
 
+def shards_leg(torch, fb, g, steps, warmup):
+    """Rows a3 + a4 of the decode step as one call over the 4 shards (after the step has left K', V' in place)."""
+    cfg = g["cfg"]
+    need = fb.fedrag_partial_attn_shards_workspace_bytes(cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.d_head,
+                                                         g["Qs"].dtype, cfg.L_q, [cfg.L_kv] * cfg.n_shards)
+    ws = torch.empty(max(need, 16), dtype=torch.uint8, device=g["Qs"].device)
+    O, lse = torch.empty_like(g["O"]), torch.empty_like(g["lse"])
+    call = lambda: fb.fedrag_partial_attn_shards(g["Qs"], g["Ks"], g["Vs"], None, O=O, lse=lse, workspace=ws)
+    for _ in range(warmup):
+        call()
+    torch.cuda.synchronize()
+    timer = CallTimer(torch)
+    for _ in range(steps):
+        timer.run("a", call)
+    torch.cuda.synchronize()
+    us = timer.summary()["a"]["avg_us"]
+    nb = cfg.n_shards * g["bytes"]["partial_attn"]
+    # the aggregation adds the partials in another order than per shard + across shards: equal to rounding
+    err = float((O - g["O"]).abs().max())
+    return {"call": "partial_attn_shards (4 shards + aggregation)", "avg_us": round(us, 2), "bytes": nb,
+            "GB/s": round(nb / us / 1e3, 1), "frac_hbm": round(nb / us / 1e3 / HBM_PEAK_GBS, 4),
+            "max_abs_diff_vs_step": err}
+
+
 def structured_leg(torch, W, fb, g, dev, steps, warmup):
     """Enc of one KV shard with the keys in structured form (S1 P1 H P2 S2 by its factors): same bytes as scramble_kv."""
     cfg = g["cfg"]
@@ -289,9 +313,10 @@ def mixed_leg(torch, W, fb, dev, steps, warmup):
 def request_leg(torch, W, fb, dev, steps, warmup, n_layers=32):
     """The attention path of one request at the largest length configuration of Section 7.1 (context 4096 + 4096 on
     two Context Owners, 128-token query segment), Llama-3-8B-shaped (32 layers, 32/8 heads of 128), batch 1:
-    per layer scramble_q -> partial_attn on the two shards -> lse_merge -> unscramble, the Inquirer's own causal
-    attention, and the 2-way merge of the two.  Once for the 128-token segment (prefill) and once for one decoded
-    token (the segment's 128 + 64 generated tokens local), each as one HIP graph of all layers."""
+    per layer scramble_q -> attention on the two shards and their aggregation -> the Inquirer's own causal attention
+    -> Dec and the aggregation of the two.  Once for the 128-token segment (prefill) and once for one decoded token
+    (the segment's 128 + 64 generated tokens local), each as one HIP graph of all layers; with the fused calls
+    (partial_attn_shards, unscramble_merge: 4 calls per layer) and call by call (8 calls per layer)."""
     B, Hq, Hkv, d, S, Lc, Lseg, Lgen = 1, 32, 8, 128, 2, 4096, 128, 64
     dt = torch.bfloat16
     gen = torch.Generator(device=dev)
@@ -303,7 +328,7 @@ def request_leg(torch, W, fb, dev, steps, warmup, n_layers=32):
     Ks = [[rnd(B, Hkv, Lc, d) for _ in range(S)] for _ in range(n_layers)]
     Vs = [[rnd(B, Hkv, Lc, d) for _ in range(S)] for _ in range(n_layers)]
 
-    def chain(Lq, L_local):
+    def chain(Lq, L_local, fused):
         Q = rnd(B, Hq, Lq, d)
         Kl = [rnd(B, Hkv, L_local, d) for _ in range(n_layers)]   # the Inquirer's own plaintext K, V per layer
         Vl = [rnd(B, Hkv, L_local, d) for _ in range(n_layers)]
@@ -319,7 +344,19 @@ def request_leg(torch, W, fb, dev, steps, warmup, n_layers=32):
         need_l = fb.fedrag_partial_attn_workspace_bytes(B, Hq, Hkv, d, dt, Lq, L_local)
         ws_l = torch.empty(max(need_l, 16), dtype=torch.uint8, device=dev)
 
+        need_s = fb.fedrag_partial_attn_shards_workspace_bytes(B, Hq, Hkv, d, dt, Lq, [Lc] * S)
+        ws_s = torch.empty(max(need_s, 16), dtype=torch.uint8, device=dev)
+
+        def layer_fused(i):
+            fb.fedrag_scramble_q(Q, phi_q, perm_q, Q_out=Qs)
+            fb.fedrag_partial_attn_shards(Qs, Ks[i], Vs[i], None, O=Om, lse=lm, workspace=ws_s)
+            fb.fedrag_local_attn(Q, Kl[i], Vl[i], None, O_part=pair_O[1], lse=pair_l[1], workspace=ws_l)
+            fb.fedrag_unscramble_merge(Om, lm, phi_vi, perm_q, pair_O[1], pair_l[1], O_out=out, lse_out=out_l,
+                                       n_kv_heads=Hkv)
+
         def layer(i):
+            if fused:
+                return layer_fused(i)
             fb.fedrag_scramble_q(Q, phi_q, perm_q, Q_out=Qs)
             for s_ in range(S):
                 fb.fedrag_partial_attn(Qs, Ks[i][s_], Vs[i][s_], None, O_part=Op[s_], lse=lp[s_], workspace=ws)
@@ -335,9 +372,11 @@ def request_leg(torch, W, fb, dev, steps, warmup, n_layers=32):
         return all_layers, out
 
     res = {"workload": "request: B1 Hq32 Hkv8 d128 bf16, 32 layers, context 4096 + 4096 on 2 shards, 128-token query "
-                       "segment; 8 C-ABI calls per layer"}
-    for name, Lq, L_local in (("segment_prefill", Lseg, Lseg), ("decode_token", 1, Lseg + Lgen)):
-        run, out = chain(Lq, L_local)
+                       "segment; 4 C-ABI calls per layer (call_by_call: 8)"}
+    for name, Lq, L_local, fused in (("segment_prefill", Lseg, Lseg, True), ("decode_token", 1, Lseg + Lgen, True),
+                                     ("segment_prefill_call_by_call", Lseg, Lseg, False),
+                                     ("decode_token_call_by_call", 1, Lseg + Lgen, False)):
+        run, out = chain(Lq, L_local, fused)
         for _ in range(max(1, warmup)):
             run()
         torch.cuda.synchronize()
@@ -573,6 +612,7 @@ def main():
                                     "synchronisations (outputs checked equal to the eager ones bit for bit); "
                                     "'eager' = the same K steps launched call by call from Python")
     line["frac_hbm"] = round(line["value"] / HBM_PEAK_GBS, 4)
+    line["shards"] = shards_leg(torch, fb, g, args.steps, args.warmup)
     line["codec"] = codec_leg(torch, fb, g, args.steps, args.warmup)
     line["structured"] = structured_leg(torch, W, fb, g, dev, args.steps, args.warmup)
     if not args.no_prefill:

@@ -190,6 +190,22 @@ fedrag_status fedrag_unscramble(const fedrag_shape* shape, int64_t L_q, const fl
                                 float* O_out, void* stream);
 
 /*
+ * The Inquirer's last step of a decoder layer's attention in one call (Section 5.3): Dec of the Compute Node's
+ * result (fedrag_unscramble on the outputs, fedrag_unpermute_lse on their log-sum-exps) followed by its
+ * aggregation (fedrag_lse_merge over two partials, the descrambled one first) with the Inquirer's own partial from
+ * fedrag_local_attn.  The values equal those of the three calls bit for bit.
+ * O_scr : fp32 [B,Hq,L_q,d] and lse_scr : fp32 [B,Hq,L_q], as the Compute Node returned them (scrambled channels,
+ * rows in the order fedrag_scramble_q gave them).  phi_v_inv, perm_q as in fedrag_unscramble.
+ * O_local, lse_local : the Inquirer's own partial, rows in their own order.  O_out, lse_out : the aggregated result,
+ * rows in their own order; they must not overlap any input (FEDRAG_ERR_ALIAS).  A row whose two log-sum-exps are both
+ * -inf gives O = 0, lse = -inf.
+ */
+fedrag_status fedrag_unscramble_merge(const fedrag_shape* shape, int64_t L_q, const float* O_scr,
+                                      const float* lse_scr, const float* phi_v_inv, const int32_t* perm_q,
+                                      const float* O_local, const float* lse_local,
+                                      float* O_out, float* lse_out, void* stream);
+
+/*
  * The structured scrambling matrix of Section 4.2 ("Our construction"),  Phi = S1 P1 H P2 S2, given by its factors
  * instead of as a d x d matrix.  One key per transform; the struct itself is HOST memory holding four DEVICE
  * pointers, each to a [n_kv_heads, d] array (4-byte aligned), with both channel permutations as gathers:

@@ -20,7 +20,7 @@ _DTYPES = {torch.float32: F32, torch.bfloat16: BF16, torch.float16: F16}
 
 EXPORTS = ("fedrag_scramble_kv", "fedrag_scramble_q", "fedrag_partial_attn",
            "fedrag_partial_attn_workspace_bytes", "fedrag_partial_attn_shards",
-           "fedrag_partial_attn_shards_workspace_bytes", "fedrag_lse_merge", "fedrag_unscramble",
+           "fedrag_partial_attn_shards_workspace_bytes", "fedrag_lse_merge", "fedrag_unscramble", "fedrag_unscramble_merge",
            "fedrag_scramble_kv_structured", "fedrag_scramble_q_structured", "fedrag_unscramble_structured",
            "fedrag_local_attn", "fedrag_unpermute_lse", "fedrag_partial_attn_varlen", "fedrag_quantize_rows",
            "fedrag_dequantize_rows", "fedrag_scramble_kv_quantized", "fedrag_scramble_kv_structured_quantized",
@@ -74,6 +74,7 @@ def load() -> ctypes.CDLL:
         lib.fedrag_partial_attn_shards_workspace_bytes.argtypes = [sp, i64, ctypes.c_int32,
                                                                    ctypes.POINTER(ctypes.c_int64)]
         lib.fedrag_partial_attn_shards_workspace_bytes.restype = ctypes.c_size_t
+        lib.fedrag_unscramble_merge.argtypes = [sp, i64, vp, vp, vp, vp, vp, vp, vp, vp, vp]
         lib.fedrag_partial_attn_varlen.argtypes = [sp, i64, i64, vp, vp, vp, vp, vp, ctypes.c_float, f32p, f32p, vp,
                                                    ctypes.c_size_t, vp]
         lib.fedrag_unpermute_lse.argtypes = [sp, i64, f32p, vp, f32p, vp]
@@ -195,6 +196,13 @@ def fedrag_partial_attn(Qs, Ks, Vs, softmax_scale: Optional[float] = None, O_par
     return O_part, lse
 
 
+def fedrag_partial_attn_shards_workspace_bytes(batch, n_q_heads, n_kv_heads, d_head, dtype, L_q, L_kv_list) -> int:
+    shape = make_shape(batch, n_q_heads, n_kv_heads, d_head, dtype)
+    n = len(L_kv_list)
+    Ls = (ctypes.c_int64 * n)(*[int(x) for x in L_kv_list])
+    return int(load().fedrag_partial_attn_shards_workspace_bytes(ctypes.byref(shape), L_q, n, Ls))
+
+
 def fedrag_partial_attn_shards(Qs, Ks_list, Vs_list, softmax_scale: Optional[float] = None, O=None, lse=None,
                                workspace=None):
     """Per-shard attention and its aggregation over the shards in one call.  Qs [B,Hq,Lq,d];
@@ -287,6 +295,20 @@ def fedrag_local_attn(Q, K, V, softmax_scale: Optional[float] = None, O_part=Non
                                   _ptr(workspace), ws_bytes, _stream())
     _check(st, "fedrag_local_attn")
     return O_part, lse
+
+
+def fedrag_unscramble_merge(O_scr, lse_scr, phi_v_inv, perm_q, O_local, lse_local, O_out=None, lse_out=None,
+                            n_kv_heads: Optional[int] = None):
+    """Dec of the remote result and its aggregation with the Inquirer's own partial, in one call."""
+    B, Hq, Lq, d = O_scr.shape
+    shape = make_shape(B, Hq, n_kv_heads or phi_v_inv.shape[0], d, F32)
+    O_out = torch.empty_like(O_scr) if O_out is None else O_out
+    lse_out = torch.empty_like(lse_scr) if lse_out is None else lse_out
+    st = load().fedrag_unscramble_merge(ctypes.byref(shape), Lq, _ptr(O_scr), _ptr(lse_scr), _ptr(phi_v_inv),
+                                        _ptr(perm_q), _ptr(O_local), _ptr(lse_local), _ptr(O_out), _ptr(lse_out),
+                                        _stream())
+    _check(st, "fedrag_unscramble_merge")
+    return O_out, lse_out
 
 
 def fedrag_unpermute_lse(lse_scr, perm_q=None, lse_out=None):

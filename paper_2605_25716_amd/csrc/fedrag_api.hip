@@ -371,6 +371,40 @@ fedrag_status fedrag_unscramble(const fedrag_shape* shape, int64_t L_q, const fl
     return dev(launch_rows_transform(j, (hipStream_t)stream));
 }
 
+fedrag_status fedrag_unscramble_merge(const fedrag_shape* shape, int64_t L_q, const float* O_scr, const float* lse_scr,
+                                      const float* phi_v_inv, const int32_t* perm_q, const float* O_local,
+                                      const float* lse_local, float* O_out, float* lse_out, void* stream) {
+    fedrag_status st = check_shape(shape, false);
+    if (st != FEDRAG_OK) return st;
+    if (L_q < 0 || L_q > INT32_MAX) return FEDRAG_ERR_SHAPE;
+    if (!O_scr || !lse_scr || !phi_v_inv || !O_local || !lse_local || !O_out || !lse_out) return FEDRAG_ERR_NULL;
+    int64_t n;
+    if (!tensor_elems(shape->batch, shape->n_q_heads, L_q, shape->d_head, &n)) return FEDRAG_ERR_SHAPE;
+    const size_t ob = (size_t)n * 4, lb = (size_t)(n / shape->d_head) * 4;
+    if (!aligned16(O_scr) || !aligned16(phi_v_inv) || !aligned16(O_out) || !aligned16(O_local) ||
+        (reinterpret_cast<uintptr_t>(perm_q) & 3u) || (reinterpret_cast<uintptr_t>(lse_scr) & 3u) ||
+        (reinterpret_cast<uintptr_t>(lse_local) & 3u) || (reinterpret_cast<uintptr_t>(lse_out) & 3u))
+        return FEDRAG_ERR_ALIAS;
+    if (overlaps(O_out, ob, O_scr, ob) || overlaps(O_out, ob, O_local, ob) || overlaps(lse_out, lb, lse_scr, lb) ||
+        overlaps(lse_out, lb, lse_local, lb))
+        return FEDRAG_ERR_ALIAS;
+    RowsJob j{};
+    j.n_jobs = 1;
+    j.X[0] = O_scr; j.Phi[0] = phi_v_inv; j.Y[0] = O_out;
+    j.X[1] = O_scr; j.Phi[1] = phi_v_inv; j.Y[1] = O_out;
+    j.perm = perm_q;
+    j.perm_batch_stride = 0;
+    j.BH = (int64_t)shape->batch * shape->n_q_heads;
+    j.H = shape->n_q_heads;
+    j.G = shape->n_q_heads / shape->n_kv_heads;
+    j.L = L_q;
+    j.D = shape->d_head;
+    j.dtype = FEDRAG_F32;
+    j.scatter = true;
+    j.merge = RowsMerge{lse_scr, O_local, lse_local, lse_out};
+    return dev(launch_rows_transform(j, (hipStream_t)stream));
+}
+
 fedrag_status fedrag_scramble_kv_structured(const fedrag_shape* shape, int64_t L_kv, const void* K, const void* V,
                                             const fedrag_structured_key* key_k, const fedrag_structured_key* key_v,
                                             const int32_t* perm_kv, int32_t n_perm, void* K_out, void* V_out,

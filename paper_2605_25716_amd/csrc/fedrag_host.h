@@ -8,6 +8,15 @@
 
 namespace fedrag {
 
+// Second partial for the scatter form (Dec followed by the Section 4.1 aggregation of two partials): row i of X has
+// log-sum-exp lse_in[bh, i]; (O_other, lse_other) is the other partial, already in destination row order.
+struct RowsMerge {
+    const float* lse_in;     // [BH, L]; NULL = plain transform
+    const float* O_other;    // [BH, L, D]
+    const float* lse_other;  // [BH, L]
+    float* lse_out;          // [BH, L]
+};
+
 // Rows-times-matrix job: up to two tensors (K and V) transformed in one launch.
 struct RowsJob {
     int n_jobs;               // 1 or 2
@@ -30,6 +39,7 @@ struct RowsJob {
     int D;                    // 64 or 128
     int dtype;                // fedrag_dtype of X / Phi / Y (ignored when scatter: fp32)
     bool scatter;             // false: Y[j] = X[perm[j]].Phi ; true: Y[perm[i]] = X[i].Phi (fp32)
+    RowsMerge merge;          // scatter, one job: aggregate every transformed row with a second partial (lse_in != NULL)
 };
 hipError_t launch_rows_transform(const RowsJob& job, hipStream_t stream);
 hipError_t launch_invert_perm(const int32_t* perm, int64_t L, int32_t* inv, hipStream_t stream);

@@ -290,11 +290,15 @@ __global__ __launch_bounds__(kScrThreads, 1) void scramble_rows_kernel(ScrambleJ
 constexpr int kF32Threads = 256;
 constexpr int kF32Rows = 32;
 
+// mg.lse_in != NULL (scatter form only): the transformed row is one of two partials of Section 4.1 and is
+// aggregated with the other one, which is already in destination order, before it is stored - the same arithmetic,
+// in the same order, as lse_merge_kernel over (this row, the other partial).
 template <int D, bool SCATTER, bool ST>
 __global__ __launch_bounds__(kF32Threads) void rows_times_matrix_f32_kernel(ScrambleJob job0, ScrambleJob job1,
                                                                             const int32_t* __restrict__ perm,
                                                                             int64_t perm_batch_stride, int H, int G,
-                                                                            int64_t L, int chunks, int tiles_per_wg) {
+                                                                            int64_t L, int chunks, int tiles_per_wg,
+                                                                            RowsMerge mg) {
     constexpr int RG = kF32Threads / D;  // row groups
     __shared__ __attribute__((aligned(16))) float xs[kF32Rows * D];
     const ScrambleJob job = blockIdx.y == 0 ? job0 : job1;
@@ -354,6 +358,27 @@ __global__ __launch_bounds__(kF32Threads) void rows_times_matrix_f32_kernel(Scra
                 acc = __builtin_fmaf(x[3], phi[k4 + 3], acc);
             }
             const int64_t dst = (SCATTER && pm) ? (int64_t)pm[j] : j;
+            if (SCATTER && mg.lse_in) {
+                const float la = mg.lse_in[(int64_t)bh * L + j];
+                const float lb = mg.lse_other[(int64_t)bh * L + dst];
+                const float M = fmaxf(fmaxf(-INFINITY, la), lb);
+                float o = 0.f, den = 0.f;
+                if (M != -INFINITY) {
+                    if (la != -INFINITY) {
+                        const float a = expf(la - M);
+                        den += a;
+                        o = __builtin_fmaf(a, acc, o);
+                    }
+                    if (lb != -INFINITY) {
+                        const float a = expf(lb - M);
+                        den += a;
+                        o = __builtin_fmaf(a, mg.O_other[((int64_t)bh * L + dst) * D + c], o);
+                    }
+                    o *= 1.0f / den;
+                }
+                acc = o;
+                if (c == 0) mg.lse_out[(int64_t)bh * L + dst] = (M == -INFINITY) ? -INFINITY : M + logf(den);
+            }
             Y[dst * D + c] = acc;
         }
     }
@@ -416,10 +441,10 @@ static hipError_t launch_rows_f32(const RowsJob& j, hipStream_t stream) {
     const ScrambleJob a = device_job(j, 0), b = device_job(j, 1);
     if (j.structured)
         hipLaunchKernelGGL((rows_times_matrix_f32_kernel<D, SCATTER, true>), grid, dim3(kF32Threads), 0, stream, a, b,
-                           j.perm, j.perm_batch_stride, j.H, j.G, j.L, chunks, tpw);
+                           j.perm, j.perm_batch_stride, j.H, j.G, j.L, chunks, tpw, j.merge);
     else
         hipLaunchKernelGGL((rows_times_matrix_f32_kernel<D, SCATTER, false>), grid, dim3(kF32Threads), 0, stream, a, b,
-                           j.perm, j.perm_batch_stride, j.H, j.G, j.L, chunks, tpw);
+                           j.perm, j.perm_batch_stride, j.H, j.G, j.L, chunks, tpw, j.merge);
     return hipGetLastError();
 }
 

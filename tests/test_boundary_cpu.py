@@ -336,3 +336,22 @@ def test_partial_attn_shards_validation_and_workspace(lib):
     # bad arguments report 0 bytes
     assert lib.fedrag_partial_attn_shards_workspace_bytes(ctypes.byref(s), 1, 17, Ls) == 0
     assert lib.fedrag_partial_attn_shards_workspace_bytes(ctypes.byref(s), 1, n, None) == 0
+
+
+def test_unscramble_merge_validation(lib):
+    s = shape(B=1, Hq=4, Hkv=2)
+    f = lib.fedrag_unscramble_merge
+    base = lambda: [ctypes.byref(s), 8, P(A), P(2 * A), P(3 * A), None, P(4 * A), P(5 * A), P(6 * A), P(7 * A), None]
+    for i in (2, 3, 4, 6, 7, 8, 9):
+        a = base(); a[i] = None
+        assert f(*a) == fb.ERR_NULL
+    a = base(); a[1] = -1
+    assert f(*a) == fb.ERR_SHAPE
+    a = base(); a[8] = P(A)            # output on top of the scrambled input
+    assert f(*a) == fb.ERR_ALIAS
+    a = base(); a[8] = P(4 * A)        # output on top of the local partial
+    assert f(*a) == fb.ERR_ALIAS
+    a = base(); a[9] = P(5 * A)        # log-sum-exp output on top of the local one
+    assert f(*a) == fb.ERR_ALIAS
+    a = base(); a[9] = P(7 * A + 2)    # misaligned
+    assert f(*a) == fb.ERR_ALIAS
