@@ -114,6 +114,9 @@ static int decode_target_wgs() {
 }
 #define FEDRAG_DEC_WGS decode_target_wgs()
 #endif
+#ifndef FEDRAG_DEC_MIN_STEPS
+#define FEDRAG_DEC_MIN_STEPS 4
+#endif
 static bool use_decode_kernel(int Hq, int Hkv, int64_t Lq) { return (int64_t)(Hq / Hkv) * Lq <= 16; }
 
 // Decode kernel: about one workgroup per compute unit over the whole launch; a run is a whole number of 128-key
@@ -146,7 +149,7 @@ KeyRuns attn_plan_runs(int B, int Hq, int Hkv, int dtype, int64_t Lq, int n, con
             quantum = kDecStride;
             per = (total + want - 1) / want;
             per = ((per + quantum - 1) / quantum) * quantum;
-            if (per < 4 * quantum) per = 4 * quantum;
+            if (per < FEDRAG_DEC_MIN_STEPS * quantum) per = FEDRAG_DEC_MIN_STEPS * quantum;
             if (per > (int64_t)1 << 22) per = (int64_t)1 << 22;
         } else {
             const int64_t wgs = (int64_t)B * Hq * ((Lq + kPreQTile - 1) / kPreQTile);

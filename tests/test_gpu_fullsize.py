@@ -163,3 +163,33 @@ def test_merge_and_unscramble_at_decode_size(oracle):
     out = fb.fedrag_unscramble(Om.to(DEV), keys.phi_v_inv.to(DEV), None)
     ref = oracle.unscramble(Om, keys.phi_v_inv, None)
     assert PT.rel_normwise(out, ref) <= PT.TOL_F32_REL
+
+
+def test_llama8b_decode_all_shards_in_one_call_full_size(oracle):
+    """fedrag_partial_attn_shards at the decode configuration's full size (4 shards of 8192 keys, 16 sequences):
+    generator data stands in for Q', K', V' (the call takes no key material), a seeded sample of
+    (sequence, KV head) units is recomputed by the oracle shard by shard and aggregated by the oracle."""
+    cfg = W.CONFIGS["llama8b_decode"]
+    dt = W.torch_dtype(cfg.dtype)
+    G = cfg.group
+    mk = lambda H, L, tid: W.activations(cfg.batch, H, L, cfg.d_head, seed=cfg.seed + 5, tensor_id=tid, outliers=False,
+                                         dtype=dt, device=DEV)
+    Q = mk(cfg.n_q_heads, cfg.L_q, W.TID_Q)
+    Ks = [mk(cfg.n_kv_heads, cfg.L_kv, W.TID_K + s) for s in range(cfg.n_shards)]
+    Vs = [mk(cfg.n_kv_heads, cfg.L_kv, W.TID_V + s) for s in range(cfg.n_shards)]
+    O, lse = fb.fedrag_partial_attn_shards(Q, Ks, Vs)
+    torch.cuda.synchronize()
+    assert torch.isfinite(O).all() and torch.isfinite(lse).all()
+    rng = np.random.default_rng(cfg.seed + 23)
+    all_units = [(b, g) for b in range(cfg.batch) for g in range(cfg.n_kv_heads)]
+    worst_o = worst_l = 0.0
+    for i in rng.choice(len(all_units), size=4, replace=False):
+        b, g = all_units[i]
+        Qu = Q[b:b + 1, g * G:(g + 1) * G].cpu()
+        parts = [oracle.partial_attn(Qu, K[b:b + 1, g:g + 1].cpu(), V[b:b + 1, g:g + 1].cpu())
+                 for K, V in zip(Ks, Vs)]
+        Or, lr = oracle.lse_merge(np.stack([p[0] for p in parts]), np.stack([p[1] for p in parts]))
+        eo, el = PT.check_attn(O[b:b + 1, g * G:(g + 1) * G], lse[b:b + 1, g * G:(g + 1) * G], Or, lr, dt,
+                               f"unit {(b, g)}")
+        worst_o, worst_l = max(worst_o, eo), max(worst_l, el)
+    print(f"shards, full size: worst O err {worst_o:.3e}, worst lse err {worst_l:.3e}")
