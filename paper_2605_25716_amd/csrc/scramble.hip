@@ -384,6 +384,153 @@ __global__ __launch_bounds__(kF32Threads) void rows_times_matrix_f32_kernel(Scra
     }
 }
 
+// The same product on the fp32 matrix cores, for slabs of at least kMfMinRows rows (the plain kernel above spends
+// its time on LDS broadcasts of the rows: 122 us for 65536 rows of 128, against 10 us of HBM time).
+// v_mfma_f32_32x32x2_f32: A 32 x 2 (lane: row lane % 32, k = lane / 32), B 2 x 32 (lane: column lane % 32, k = lane / 32),
+// C 32 x 32 (lane: column lane % 32, register r: row 8 (r / 4) + 4 (lane / 32) + r % 4).  Wave w of the 4 owns the
+// 32-column slice w % (D / 32) of the output and keeps that slice of Phi in registers as B operands (D / 2 of them);
+// the rows of a step (32 for D = 128, two tiles of 32 for D = 64) are staged once in LDS, coalesced, and every wave
+// reads its tile's rows from there 16 bytes at a time: the 4 floats are the A operands of 4 steps, contraction index
+// 8 j + 4 (lane / 32) + e for read j, element e.  The next step's rows are fetched into registers before the MFMAs
+// of the current one and go to the other LDS buffer after them: one barrier per step.
+constexpr int kMfMinRows = 64;
+#ifndef FEDRAG_MF_WANT_WGS
+#define FEDRAG_MF_WANT_WGS 512
+#endif
+
+template <int D, bool SCATTER, bool ST>
+__global__ __launch_bounds__(kF32Threads) void rows_times_matrix_mfma_f32_kernel(ScrambleJob job0, ScrambleJob job1,
+                                                                                 const int32_t* __restrict__ perm,
+                                                                                 int64_t perm_batch_stride, int H,
+                                                                                 int G, int64_t L, int chunks,
+                                                                                 int steps_per_wg, RowsMerge mg) {
+    constexpr int SL = D / 32;         // 32-column slices of the output
+    constexpr int RT = 4 / SL;         // 32-row tiles per step
+    constexpr int TR = 32 * RT;        // rows per step
+    constexpr int LDP = D + 4;         // padded LDS row, floats: 16-byte reads of 8 rows cover all banks once
+    constexpr int NJ = D / 8;          // 16-byte operand reads per row
+    constexpr int CPR = D / 4;         // 16-byte chunks per row
+    constexpr int CPT = TR * CPR / kF32Threads;  // chunks per thread per step
+    static_assert(CPT * kF32Threads == TR * CPR, "a step's rows divide evenly over the threads");
+    __shared__ __attribute__((aligned(16))) float xs[2][TR * LDP];
+    __shared__ int32_t p_in_inv[ST ? D : 1];
+    __shared__ float s_in[ST ? D : 1];
+
+    const ScrambleJob job = blockIdx.y == 0 ? job0 : job1;
+    const int tid = threadIdx.x;
+    const int wave = tid / kWave;
+    const int lane = tid % kWave;
+    const int n = lane % 32;
+    const int kk = lane / 32;
+    const int slice = wave % SL;
+    const int rt = wave / SL;
+    const int bh = blockIdx.x / chunks;
+    const int chunk = blockIdx.x % chunks;
+    const int b = bh / H;
+    const int h = bh % H;
+    const int64_t first_row = (int64_t)chunk * steps_per_wg * TR;
+    if (first_row >= L) return;  // workgroup-uniform, before any barrier
+    int n_steps = (int)((L - first_row + TR - 1) / TR);
+    if (n_steps > steps_per_wg) n_steps = steps_per_wg;
+
+    const int col = 32 * slice + n;  // this lane's output column
+    float phi[NJ][4];
+    if (ST) {  // column `col` of S1 P1 H P2 S2, generated from the key
+        const int32_t* g1 = job.p_in + (int64_t)(h / G) * D;
+        for (int k = tid; k < D; k += kF32Threads) {
+            p_in_inv[g1[k] & (D - 1)] = k;
+            s_in[k] = job.s_in[(int64_t)(h / G) * D + k];
+        }
+        __syncthreads();
+        const int m = job.p_out[(int64_t)(h / G) * D + col] & (D - 1);
+        const float post = job.s_out[(int64_t)(h / G) * D + col] * (D == 128 ? 0.08838834764831845f : 0.125f);
+#pragma unroll
+        for (int j = 0; j < NJ; ++j)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int k = 8 * j + 4 * kk + e;
+                phi[j][e] = structured_entry(s_in[k], p_in_inv[k], m) * post;
+            }
+    } else {
+        const float* P = (const float*)job.Phi + (int64_t)(h / G) * D * D;
+#pragma unroll
+        for (int j = 0; j < NJ; ++j)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) phi[j][e] = P[(8 * j + 4 * kk + e) * D + col];
+    }
+
+    const float* X = (const float*)job.X + (int64_t)bh * L * D;
+    float* Y = (float*)job.Y + (int64_t)bh * L * D;
+    const int32_t* pm = perm ? perm + (int64_t)b * perm_batch_stride : nullptr;
+
+    auto fetch = [&](int64_t row0, f32x4_t (&buf)[CPT]) {
+#pragma unroll
+        for (int q = 0; q < CPT; ++q) {
+            const int e = tid + q * kF32Threads;
+            int64_t j = row0 + e / CPR;
+            if (j >= L) j = L - 1;  // rows past the end: computed on a real row, never stored
+            const int64_t src = (!SCATTER && pm) ? (int64_t)pm[j] : j;
+            buf[q] = *(const f32x4_t*)(X + src * D + (e % CPR) * 4);
+        }
+    };
+    auto stash = [&](int slot, const f32x4_t (&buf)[CPT]) {
+#pragma unroll
+        for (int q = 0; q < CPT; ++q) {
+            const int e = tid + q * kF32Threads;
+            *(f32x4_t*)(&xs[slot][(e / CPR) * LDP + (e % CPR) * 4]) = buf[q];
+        }
+    };
+
+    f32x4_t buf[CPT];
+    fetch(first_row, buf);
+    stash(0, buf);
+    __syncthreads();
+    for (int s_ = 0; s_ < n_steps; ++s_) {
+        const int64_t row0 = first_row + (int64_t)s_ * TR;
+        const bool more = s_ + 1 < n_steps;
+        if (more) fetch(row0 + TR, buf);
+        const float* xr = &xs[s_ & 1][(32 * rt + n) * LDP + 4 * kk];
+        f32x16_t acc = zero_vec<f32x16_t>();
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) {
+            const f32x4_t a = *(const f32x4_t*)(xr + 8 * j);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[e], phi[j][e], acc, 0, 0, 0);
+        }
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int64_t j = row0 + 32 * rt + 8 * (r / 4) + 4 * kk + (r % 4);
+            if (j >= L) continue;
+            const int64_t dst = (SCATTER && pm) ? (int64_t)pm[j] : j;
+            float v = acc[r];
+            if (SCATTER && mg.lse_in) {
+                const float la = mg.lse_in[(int64_t)bh * L + j];
+                const float lb = mg.lse_other[(int64_t)bh * L + dst];
+                const float M = fmaxf(fmaxf(-INFINITY, la), lb);
+                float o = 0.f, den = 0.f;
+                if (M != -INFINITY) {
+                    if (la != -INFINITY) {
+                        const float a = expf(la - M);
+                        den += a;
+                        o = __builtin_fmaf(a, v, o);
+                    }
+                    if (lb != -INFINITY) {
+                        const float a = expf(lb - M);
+                        den += a;
+                        o = __builtin_fmaf(a, mg.O_other[((int64_t)bh * L + dst) * D + col], o);
+                    }
+                    o *= 1.0f / den;
+                }
+                v = o;
+                if (col == 0) mg.lse_out[(int64_t)bh * L + dst] = (M == -INFINITY) ? -INFINITY : M + logf(den);
+            }
+            Y[dst * D + col] = v;
+        }
+        if (more) stash((s_ + 1) & 1, buf);
+        __syncthreads();
+    }
+}
+
 __global__ void invert_perm_kernel(const int32_t* __restrict__ perm, int64_t L, int32_t* __restrict__ inv) {
     const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (j < L) inv[perm[j]] = (int32_t)j;
@@ -429,7 +576,30 @@ static hipError_t launch_scramble16(const RowsJob& j, hipStream_t stream) {
 }
 
 template <int D, bool SCATTER>
+static hipError_t launch_rows_mfma_f32(const RowsJob& j, hipStream_t stream) {
+    constexpr int TR = 32 * (4 / (D / 32));  // rows per workgroup step
+    const int64_t steps = (j.L + TR - 1) / TR;
+    // about two workgroups per compute unit, at most 64 steps each (a workgroup loads its slice of Phi once)
+    const int64_t want_wgs = FEDRAG_MF_WANT_WGS;
+    const int64_t total = steps * j.BH * j.n_jobs;
+    int spw = (int)(total / want_wgs);
+    if (spw < 1) spw = 1;
+    if (spw > 64) spw = 64;
+    const int chunks = ceil_div_i64(steps, spw);
+    dim3 grid((unsigned)(j.BH * chunks), (unsigned)j.n_jobs);
+    const ScrambleJob a = device_job(j, 0), b = device_job(j, 1);
+    if (j.structured)
+        hipLaunchKernelGGL((rows_times_matrix_mfma_f32_kernel<D, SCATTER, true>), grid, dim3(kF32Threads), 0, stream, a,
+                           b, j.perm, j.perm_batch_stride, j.H, j.G, j.L, chunks, spw, j.merge);
+    else
+        hipLaunchKernelGGL((rows_times_matrix_mfma_f32_kernel<D, SCATTER, false>), grid, dim3(kF32Threads), 0, stream,
+                           a, b, j.perm, j.perm_batch_stride, j.H, j.G, j.L, chunks, spw, j.merge);
+    return hipGetLastError();
+}
+
+template <int D, bool SCATTER>
 static hipError_t launch_rows_f32(const RowsJob& j, hipStream_t stream) {
+    if (j.L >= kMfMinRows) return launch_rows_mfma_f32<D, SCATTER>(j, stream);
     const int64_t tiles = (j.L + kF32Rows - 1) / kF32Rows;
     const int64_t want_wgs = 2048;
     const int64_t total = tiles * j.BH * j.n_jobs;

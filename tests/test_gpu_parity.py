@@ -179,7 +179,8 @@ def test_lse_merge(oracle, d, S, rows_shape):
     assert not torch.isnan(Om).any() and not torch.isnan(lm).any()
 
 
-@pytest.mark.parametrize("d,Hq,Hkv,Lq", [(128, 8, 2, 1), (128, 4, 2, 77), (64, 4, 4, 40)])
+@pytest.mark.parametrize("d,Hq,Hkv,Lq", [(128, 8, 2, 1), (128, 4, 2, 77), (64, 4, 4, 40), (128, 4, 2, 300),
+                                           (64, 4, 4, 130)])
 def test_unscramble(oracle, d, Hq, Hkv, Lq):
     keys = W.make_keys(Hkv, d, Lq, 8, 1, seed=5 + Lq, dtype=torch.bfloat16)
     g = torch.Generator().manual_seed(12)
