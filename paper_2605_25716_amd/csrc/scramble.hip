@@ -283,11 +283,76 @@ __global__ __launch_bounds__(kScrThreads, 1) void scramble_rows_kernel(ScrambleJ
         if (i + NBUF + j < n_mine) step(buf[j], i + NBUF + j, false, idx_next);
 }
 
+// A handful of rows per head (the decoding step's queries): the tiled kernel above would stage a whole matrix per
+// workgroup through LDS and registers for one or two rows.  Here a workgroup takes one (sequence, head) slab of at
+// most kFewRows rows; thread (c, rg) owns output column c, reads column c of Phi straight from memory (coalesced
+// over c, every load independent), takes the rows from LDS as fp32 broadcasts and narrows each fp32 sum once.
+constexpr int kFewRows = 16;
+constexpr int kF32Threads = 256;  // workgroup size of the plain-FMA kernels
+
+template <class T, int D, bool ST>
+__global__ __launch_bounds__(kF32Threads) void scramble_few_rows_kernel(ScrambleJob job0, ScrambleJob job1,
+                                                                        const int32_t* __restrict__ perm,
+                                                                        int64_t perm_batch_stride, int H, int G,
+                                                                        int L) {
+    typedef typename T::elem elem;
+    constexpr int RG = kF32Threads / D;
+    __shared__ float xs[kFewRows * D];
+    __shared__ int32_t p_in_inv[ST ? D : 1];
+    __shared__ float s_in[ST ? D : 1];
+    const ScrambleJob job = blockIdx.y == 0 ? job0 : job1;
+    const int tid = threadIdx.x;
+    const int c = tid % D;
+    const int rg = tid / D;
+    const int bh = blockIdx.x;
+    const int b = bh / H;
+    const int h = bh % H;
+    const elem* X = (const elem*)job.X + (int64_t)bh * L * D;
+    elem* Y = (elem*)job.Y + (int64_t)bh * L * D;
+    const int32_t* pm = perm ? perm + (int64_t)b * perm_batch_stride : nullptr;
+    for (int e = tid; e < L * D; e += kF32Threads) {
+        const int j = e / D;
+        const int64_t src = pm ? (int64_t)pm[j] : j;
+        xs[e] = T::to_float(X[src * D + e % D]);
+    }
+    float phi[D];
+    float post = 1.0f;
+    if (ST) {
+        const int32_t* g1 = job.p_in + (int64_t)(h / G) * D;
+        for (int k = tid; k < D; k += kF32Threads) {
+            p_in_inv[g1[k] & (D - 1)] = k;
+            // the matrix entries are +-scale_in narrowed to the storage type, as in the tiled kernel
+            s_in[k] = T::to_float(T::from_float(job.s_in[(int64_t)(h / G) * D + k]));
+        }
+        __syncthreads();
+        const int m = job.p_out[(int64_t)(h / G) * D + c] & (D - 1);
+        post = job.s_out[(int64_t)(h / G) * D + c] * (D == 128 ? 0.08838834764831845f : 0.125f);
+#pragma unroll
+        for (int k = 0; k < D; ++k) phi[k] = structured_entry(s_in[k], p_in_inv[k], m);
+    } else {
+        const elem* P = (const elem*)job.Phi + (int64_t)(h / G) * D * D;
+#pragma unroll
+        for (int k = 0; k < D; ++k) phi[k] = T::to_float(P[k * D + c]);
+    }
+    __syncthreads();
+    for (int r = rg; r < L; r += RG) {
+        float acc = 0.f;
+#pragma unroll
+        for (int k4 = 0; k4 < D; k4 += 4) {
+            const f32x4_t x = *(const f32x4_t*)(&xs[r * D + k4]);
+            acc = __builtin_fmaf(x[0], phi[k4 + 0], acc);
+            acc = __builtin_fmaf(x[1], phi[k4 + 1], acc);
+            acc = __builtin_fmaf(x[2], phi[k4 + 2], acc);
+            acc = __builtin_fmaf(x[3], phi[k4 + 3], acc);
+        }
+        Y[(int64_t)r * D + c] = T::from_float(ST ? acc * post : acc);
+    }
+}
+
 // fp32 rows times fp32 matrix with plain FMAs (fp32 storage path of Enc, and Dec for every storage type).
 // Thread (c, rg) owns output column c and holds column c of Phi in registers; rows are broadcast from LDS.
 //   SCATTER == false: Y[j]       = X[perm[j]] . Phi   (perm NULL = identity)
 //   SCATTER == true : Y[perm[i]] = X[i] . Phi
-constexpr int kF32Threads = 256;
 constexpr int kF32Rows = 32;
 
 // mg.lse_in != NULL (scatter form only): the transformed row is one of two partials of Section 4.1 and is
@@ -545,6 +610,17 @@ static ScrambleJob device_job(const RowsJob& j, int i) {
 
 template <class T, int D>
 static hipError_t launch_scramble16(const RowsJob& j, hipStream_t stream) {
+    if (j.L <= kFewRows && j.quant_bits == 0) {
+        dim3 grid((unsigned)j.BH, (unsigned)j.n_jobs);
+        const ScrambleJob a = device_job(j, 0), b = device_job(j, 1);
+        if (j.structured)
+            hipLaunchKernelGGL((scramble_few_rows_kernel<T, D, true>), grid, dim3(kF32Threads), 0, stream, a, b, j.perm,
+                               j.perm_batch_stride, j.H, j.G, (int)j.L);
+        else
+            hipLaunchKernelGGL((scramble_few_rows_kernel<T, D, false>), grid, dim3(kF32Threads), 0, stream, a, b, j.perm,
+                               j.perm_batch_stride, j.H, j.G, (int)j.L);
+        return hipGetLastError();
+    }
     const int64_t rows_per_pass = kScrWaves * kScrRows;  // rows one workgroup covers per ring step
     const int64_t passes = (j.L + rows_per_pass - 1) / rows_per_pass;  // per [L, d] slab
     // about one workgroup per CU over the whole launch, split evenly over (job, head); never more members than a
