@@ -152,7 +152,8 @@ KeyRuns attn_plan_runs(int B, int Hq, int Hkv, int dtype, int64_t Lq, int n, con
             if (per < FEDRAG_DEC_MIN_STEPS * quantum) per = FEDRAG_DEC_MIN_STEPS * quantum;
             if (per > (int64_t)1 << 22) per = (int64_t)1 << 22;
         } else {
-            const int64_t wgs = (int64_t)B * Hq * ((Lq + kPreQTile - 1) / kPreQTile);
+            // the query heads of a KV head form one run of G * Lq rows (see launch_prefill_t)
+            const int64_t wgs = (int64_t)B * Hkv * (((int64_t)(Hq / Hkv) * Lq + kPreQTile - 1) / kPreQTile);
             quantum = kPreK;
             if (wgs > 0 && wgs * 2 <= cus) {
                 const int64_t want = cus / wgs;

@@ -422,7 +422,13 @@ template <class T, int D, bool CAUSAL>
 static hipError_t launch_prefill_t(const AttnProblem& p, hipStream_t stream) {
     typedef typename T::elem elem;
     const float scale_log2 = p.scale * kLog2e;
-    const int q_tiles = (int)((p.Lq + kPreQTile - 1) / kPreQTile);
+    // Without a mask or per-sequence query counts a row's position in its head means nothing, and the query heads of
+    // a KV head are contiguous in Q, O and lse: the kernel then sees one head of G * Lq rows per KV head, so that
+    // short segments fill their 256-row tiles (128 queries x 4 heads: 2 full tiles instead of 4 half-empty ones).
+    const bool pack_group = !CAUSAL && !p.q_lens;
+    const int Hq_k = pack_group ? p.Hkv : p.Hq;
+    const int64_t Lq_k = pack_group ? (int64_t)(p.Hq / p.Hkv) * p.Lq : p.Lq;
+    const int q_tiles = (int)((Lq_k + kPreQTile - 1) / kPreQTile);
     const int n_units = p.B * p.Hkv;
     // several runs: only the plain call (every key of every sequence, every query row, no mask) takes them
     KeyRuns runs = attn_runs_of(p);
@@ -443,10 +449,10 @@ static hipError_t launch_prefill_t(const AttnProblem& p, hipStream_t stream) {
         Odst = (float*)p.workspace;
         Ldst = Odst + (size_t)splits * rows * D;
     }
-    const int per_unit = (p.Hq / p.Hkv) * q_tiles * splits;
+    const int per_unit = (Hq_k / p.Hkv) * q_tiles * splits;
     const int64_t grid = (int64_t)8 * ((n_units + 7) / 8) * per_unit;
     hipLaunchKernelGGL((prefill_attn_kernel<T, D, CAUSAL>), dim3((unsigned)grid), dim3(kPreThreads), 0, stream,
-                       (const elem*)p.Q, runs, p.Hq, p.Hkv, p.Lq, p.kv_lens, p.q_lens, q_tiles, n_units, scale_log2,
+                       (const elem*)p.Q, runs, Hq_k, p.Hkv, Lq_k, p.kv_lens, p.q_lens, q_tiles, n_units, scale_log2,
                        Odst, Ldst);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess || splits == 1) return e;

@@ -286,9 +286,9 @@ def test_workspace_size_of_prefill_shapes(lib):
     def need(B, Hq, Hkv, d, Lq, L, dt=fb.BF16):
         s = fb.make_shape(B, Hq, Hkv, d, dt)
         return int(lib.fedrag_partial_attn_workspace_bytes(ctypes.byref(s), Lq, L))
-    # 32 workgroups, 64 tiles -> 8 runs of 8 tiles
-    assert need(1, 32, 8, 128, 128, 4096) == 8 * 32 * 128 * (128 + 1) * 4
-    # 4 workgroups, 24 tiles -> runs of at least 4 tiles -> 6 runs
+    # 8 KV heads x 2 tiles of the 4 x 128 rows of a group = 16 workgroups, 64 tiles -> 16 runs of 4 tiles
+    assert need(1, 32, 8, 128, 128, 4096) == 16 * 32 * 128 * (128 + 1) * 4
+    # 2 workgroups, 24 tiles -> runs of at least 4 tiles -> 6 runs
     assert need(1, 4, 2, 128, 70, 1500) == 6 * 4 * 70 * (128 + 1) * 4
     # fewer than 8 tiles: one run
     assert need(1, 4, 2, 128, 70, 256) == 0
