@@ -38,6 +38,9 @@ def parse():
     ap.add_argument("--no-prefill", action="store_true", help="skip the RAG-prefill leg")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replay of the step")
+    ap.add_argument("--legs", default="all",
+                    help="comma-separated extra legs to run after the decode step: shards, codec, structured, rerank, "
+                         "local_attn, request, mixed70b, prefill (default: all; 'none' for the step alone)")
     ap.add_argument("--cpu-shards", type=int, default=4, help="KV shards (all sequences) the oracle is timed on")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run one 1 GiB device-to-device copy kernel before the timed region: a kernel of known "
@@ -620,15 +623,31 @@ def main():
                                     "synchronisations (outputs checked equal to the eager ones bit for bit); "
                                     "'eager' = the same K steps launched call by call from Python")
     line["frac_hbm"] = round(line["value"] / HBM_PEAK_GBS, 4)
-    line["shards"] = shards_leg(torch, fb, g, args.steps, args.warmup)
-    line["codec"] = codec_leg(torch, fb, g, args.steps, args.warmup)
-    line["structured"] = structured_leg(torch, W, fb, g, dev, args.steps, args.warmup)
-    if not args.no_prefill:
-        line["rerank"] = rerank_leg(torch, W, fb, dev, max(5, args.steps // 2), args.warmup)
-        line["local_attn"] = local_attn_leg(torch, W, fb, dev, max(5, args.steps // 2), args.warmup)
-        line["request"] = request_leg(torch, W, fb, dev, max(5, args.steps // 2), args.warmup)
-        line["mixed70b"] = mixed_leg(torch, W, fb, dev, max(5, args.steps // 2), args.warmup)
-        line["prefill"] = prefill_leg(torch, W, fb, dev, max(5, args.steps // 2), args.warmup)
+    all_legs = ("shards", "codec", "structured", "rerank", "local_attn", "request", "mixed70b", "prefill")
+    want = set(all_legs) if args.legs == "all" else {x for x in args.legs.split(",") if x and x != "none"}
+    unknown = want - set(all_legs)
+    if unknown:
+        print(f"bench.py: unknown legs {sorted(unknown)}; known: {', '.join(all_legs)}", file=sys.stderr)
+        sys.exit(2)
+    if args.no_prefill:
+        want -= {"rerank", "local_attn", "request", "mixed70b", "prefill"}
+    half = max(5, args.steps // 2)
+    if "shards" in want:
+        line["shards"] = shards_leg(torch, fb, g, args.steps, args.warmup)
+    if "codec" in want:
+        line["codec"] = codec_leg(torch, fb, g, args.steps, args.warmup)
+    if "structured" in want:
+        line["structured"] = structured_leg(torch, W, fb, g, dev, args.steps, args.warmup)
+    if "rerank" in want:
+        line["rerank"] = rerank_leg(torch, W, fb, dev, half, args.warmup)
+    if "local_attn" in want:
+        line["local_attn"] = local_attn_leg(torch, W, fb, dev, half, args.warmup)
+    if "request" in want:
+        line["request"] = request_leg(torch, W, fb, dev, half, args.warmup)
+    if "mixed70b" in want:
+        line["mixed70b"] = mixed_leg(torch, W, fb, dev, half, args.warmup)
+    if "prefill" in want:
+        line["prefill"] = prefill_leg(torch, W, fb, dev, half, args.warmup)
     if not args.no_cpu:
         line["cpu_baseline"] = cpu_leg(torch, W, g, args.cpu_shards)
     print(json.dumps(line))
