@@ -73,3 +73,50 @@ def test_decode_chain_replays_from_a_hip_graph():
         torch.cuda.synchronize()
         assert torch.equal(g["out"], ref_out), f"replay {rep}: output differs from the eager result"
         assert torch.equal(g["lse"], ref_lse), f"replay {rep}: lse differs from the eager result"
+
+
+def fused_chain(g):
+    """scramble_q -> attention over all shards with their aggregation -> the Inquirer's own attention -> Dec and the
+    aggregation of the two, for a 70-token segment (prefill kernel with key runs, fp32 matrix-core Dec)."""
+    fb.fedrag_scramble_q(g["Q"], g["phi_q"], g["perm_q"], Q_out=g["Qs"])
+    fb.fedrag_partial_attn_shards(g["Qs"], g["Ksl"], g["Vsl"], None, O=g["O"], lse=g["lse"], workspace=g["ws"])
+    fb.fedrag_local_attn(g["Q"], g["Kl"], g["Vl"], None, O_part=g["Ol"], lse=g["ll"])
+    fb.fedrag_unscramble_merge(g["O"], g["lse"], g["phi_v_inv"], g["perm_q"], g["Ol"], g["ll"], O_out=g["out"],
+                               lse_out=g["out_l"], n_kv_heads=g["Hkv"])
+
+
+def test_fused_segment_chain_replays_from_a_hip_graph():
+    B, Hq, Hkv, d, Lq, Ls = 1, 8, 2, 128, 70, [1500, 700, 64]
+    dt = torch.bfloat16
+    keys = W.make_keys(Hkv, d, Lq, max(Ls), len(Ls), seed=777, dtype=dt, permute_q=True)
+    mk = lambda H, L, tid: W.activations(B, H, L, d, seed=777, tensor_id=tid, outliers=False, dtype=dt, device=DEV)
+    g = {"Hkv": Hkv, "Q": mk(Hq, Lq, W.TID_Q), "Kl": mk(Hkv, Lq, 50), "Vl": mk(Hkv, Lq, 51),
+         "Ksl": [mk(Hkv, L, W.TID_K + i) for i, L in enumerate(Ls)],
+         "Vsl": [mk(Hkv, L, W.TID_V + i) for i, L in enumerate(Ls)],
+         "phi_q": keys.phi_q.to(DEV), "phi_v_inv": keys.phi_v_inv.to(DEV), "perm_q": keys.perm_q.to(DEV)}
+    f32 = lambda *s: torch.empty(s, dtype=torch.float32, device=DEV)
+    g["Qs"] = torch.empty_like(g["Q"])
+    g["O"], g["lse"], g["Ol"], g["ll"] = f32(B, Hq, Lq, d), f32(B, Hq, Lq), f32(B, Hq, Lq, d), f32(B, Hq, Lq)
+    g["out"], g["out_l"] = f32(B, Hq, Lq, d), f32(B, Hq, Lq)
+    need = fb.fedrag_partial_attn_shards_workspace_bytes(B, Hq, Hkv, d, dt, Lq, Ls)
+    assert need > 0
+    g["ws"] = torch.empty(need, dtype=torch.uint8, device=DEV)
+    fused_chain(g)
+    torch.cuda.synchronize()
+    ref_out, ref_lse = g["out"].clone(), g["out_l"].clone()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            fused_chain(g)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    for rep in range(3):
+        for k in ("Qs", "O", "lse", "Ol", "ll", "out", "out_l"):
+            g[k].fill_(float(rep + 1))
+        g["ws"].fill_(rep + 1)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(g["out"], ref_out) and torch.equal(g["out_l"], ref_lse), f"replay {rep} differs"
