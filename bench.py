@@ -40,7 +40,7 @@ def parse():
     ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replay of the step")
     ap.add_argument("--legs", default="all",
                     help="comma-separated extra legs to run after the decode step: shards, codec, structured, rerank, "
-                         "local_attn, request, mixed70b, prefill (default: all; 'none' for the step alone)")
+                         "local_attn, request, mixed70b, prefill, long_decode (default: all; 'none' for the step alone)")
     ap.add_argument("--cpu-shards", type=int, default=4, help="KV shards (all sequences) the oracle is timed on")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run one 1 GiB device-to-device copy kernel before the timed region: a kernel of known "
@@ -412,6 +412,55 @@ def request_leg(torch, W, fb, dev, steps, warmup, n_layers=32):
     return res
 
 
+def long_decode_leg(torch, W, fb, dev, steps, warmup):
+    """Long-context decode (B64, 32/8 heads, d128, 8 shards x 32768 tokens, bf16): rows a3 + a4 with all 64 GiB of
+    K', V' resident, as one call over the 8 shards and shard by shard."""
+    cfg = W.CONFIGS["long_decode"]
+    dt = W.torch_dtype(cfg.dtype)
+    B, Hq, Hkv, d, S, L = cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.d_head, cfg.n_shards, cfg.L_kv
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(cfg.seed)
+
+    def rnd(*shape):   # drawn in slabs so that the fp32 intermediate stays small
+        out = torch.empty(shape, dtype=dt, device=dev)
+        for b in range(shape[0]):
+            out[b] = torch.randn(shape[1:], generator=gen, device=dev).to(dt)
+        return out
+    Q = rnd(B, Hq, 1, d)
+    Ks = [rnd(B, Hkv, L, d) for _ in range(S)]
+    Vs = [rnd(B, Hkv, L, d) for _ in range(S)]
+    O, lse = torch.empty((B, Hq, 1, d), dtype=torch.float32, device=dev), torch.empty((B, Hq, 1), dtype=torch.float32, device=dev)
+    Op = torch.empty((S, B, Hq, 1, d), dtype=torch.float32, device=dev)
+    lp = torch.empty((S, B, Hq, 1), dtype=torch.float32, device=dev)
+    need = fb.fedrag_partial_attn_shards_workspace_bytes(B, Hq, Hkv, d, dt, 1, [L] * S)
+    ws = torch.empty(max(need, 16), dtype=torch.uint8, device=dev)
+    need1 = fb.fedrag_partial_attn_workspace_bytes(B, Hq, Hkv, d, dt, 1, L)
+    ws1 = torch.empty(max(need1, 16), dtype=torch.uint8, device=dev)
+
+    def one_call():
+        fb.fedrag_partial_attn_shards(Q, Ks, Vs, None, O=O, lse=lse, workspace=ws)
+
+    def per_shard():
+        for s_ in range(S):
+            fb.fedrag_partial_attn(Q, Ks[s_], Vs[s_], None, O_part=Op[s_], lse=lp[s_], workspace=ws1)
+        fb.fedrag_lse_merge(Op, lp, n_kv_heads=Hkv, O_out=O, lse_out=lse)
+
+    out = {"workload": "long_decode: B64 Hq32 Hkv8 d128 Lq1, 8 shards x 32768 tokens, bf16 (64 GiB of K', V')"}
+    byts = 4.0 * d * B * Hkv * L * S
+    for name, fn in (("one_call", one_call), ("shard_by_shard", per_shard)):
+        for _ in range(max(1, warmup // 2)):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            fn()
+        torch.cuda.synchronize()
+        ms = 1e3 * (time.perf_counter() - t0) / steps
+        out[name] = {"ms": round(ms, 3), "GB/s": round(byts / ms / 1e6, 1),
+                     "frac_hbm": round(byts / ms / 1e6 / HBM_PEAK_GBS, 4)}
+    return out
+
+
 def codec_leg(torch, fb, g, steps, warmup):
     """Transport codec on one shard's K' ([16, 8, 8192, 128] bf16): quantise to 8 bits and back, bytes = read + write."""
     X = g["Ks"][0]
@@ -623,14 +672,15 @@ def main():
                                     "synchronisations (outputs checked equal to the eager ones bit for bit); "
                                     "'eager' = the same K steps launched call by call from Python")
     line["frac_hbm"] = round(line["value"] / HBM_PEAK_GBS, 4)
-    all_legs = ("shards", "codec", "structured", "rerank", "local_attn", "request", "mixed70b", "prefill")
+    all_legs = ("shards", "codec", "structured", "rerank", "local_attn", "request", "mixed70b", "prefill",
+                "long_decode")
     want = set(all_legs) if args.legs == "all" else {x for x in args.legs.split(",") if x and x != "none"}
     unknown = want - set(all_legs)
     if unknown:
         print(f"bench.py: unknown legs {sorted(unknown)}; known: {', '.join(all_legs)}", file=sys.stderr)
         sys.exit(2)
     if args.no_prefill:
-        want -= {"rerank", "local_attn", "request", "mixed70b", "prefill"}
+        want -= {"rerank", "local_attn", "request", "mixed70b", "prefill", "long_decode"}
     half = max(5, args.steps // 2)
     if "shards" in want:
         line["shards"] = shards_leg(torch, fb, g, args.steps, args.warmup)
@@ -650,6 +700,10 @@ def main():
         line["prefill"] = prefill_leg(torch, W, fb, dev, half, args.warmup)
     if not args.no_cpu:
         line["cpu_baseline"] = cpu_leg(torch, W, g, args.cpu_shards)
+    if "long_decode" in want:   # last: it takes 64 GiB of device memory
+        del g
+        torch.cuda.empty_cache()
+        line["long_decode"] = long_decode_leg(torch, W, fb, dev, 5, args.warmup)
     print(json.dumps(line))
 
 
