@@ -43,14 +43,14 @@ struct DecTile {
 };
 template <class T, int D>
 struct DecTile<T, D, 8> {
-    u32x2_t kc[2][D / 32];  // 8 codes per (16-key tile, contraction step)
+    u32x4_t kc[2][D / 64];  // 16 codes per (16-key tile, pair of contraction steps): one 16-byte load each
     u32x2_t vc[8];          // 8 codes per key (D = 128: DCH = 8 elements per lane and key)
     u32x2_t kp[2];          // (scale, lo) as bits, of key rows 16 mt + lr
     u32x2_t vp[8];          // of this lane's eight keys
 };
 template <class T, int D>
 struct DecTile<T, D, 4> {
-    uint32_t kc[2][D / 32];
+    u32x4_t kc[2];          // 32 codes per 16-key tile (all four contraction steps): one 16-byte load
     uint32_t vc[8];
     u32x2_t kp[2];
     u32x2_t vp[8];
@@ -80,12 +80,21 @@ __device__ __forceinline__ typename T::vec8 dequant8(u32x2_t w, u32x2_t prm) {  
 }
 template <class T>
 __device__ __forceinline__ typename T::vec8 dequant8(uint32_t w, u32x2_t prm) {  // 4-bit codes
+    // even and odd nibbles spread to bytes first (3 instructions for 8 codes), so that each code then converts with
+    // one byte-to-float instruction
+    const uint32_t ev = w & 0x0f0f0f0fu, od = (w >> 4) & 0x0f0f0f0fu;
     uint32_t q[8];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) q[e] = (w >> (4 * e)) & 15u;
+    for (int e = 0; e < 8; ++e) q[e] = ((e % 2 ? od : ev) >> (8 * (e / 2))) & 255u;
     return dequant_codes<T>(q, prm);
 }
 
+#ifndef FEDRAG_DEC_NBUF_Q8
+#define FEDRAG_DEC_NBUF_Q8 2
+#endif
+#ifndef FEDRAG_DEC_NBUF_Q4
+#define FEDRAG_DEC_NBUF_Q4 2
+#endif
 #ifndef FEDRAG_DEC_NBUF
 #define FEDRAG_DEC_NBUF 2   // register tile sets per wave
 #endif
@@ -113,7 +122,7 @@ __global__ __launch_bounds__(kDecThreads, FEDRAG_DEC_OCC) void decode_attn_kerne
     constexpr int NW = DCH / 2;  // 32-bit words of that
     constexpr int ROWB = QB ? D * QB / 8 : D * 2;  // bytes per row of K' / V' as stored (values, or codes)
     constexpr int TILEB = kDecTile * ROWB;
-    constexpr int NBUF = FEDRAG_DEC_NBUF;
+    constexpr int NBUF = QB == 0 ? FEDRAG_DEC_NBUF : (QB == 8 ? FEDRAG_DEC_NBUF_Q8 : FEDRAG_DEC_NBUF_Q4);
     constexpr int AUX = FEDRAG_DEC_AUX;
 
     __shared__ float sm_m[kDecWaves][16];
@@ -160,10 +169,18 @@ __global__ __launch_bounds__(kDecThreads, FEDRAG_DEC_OCC) void decode_attn_kerne
     const char* Vb = (const char*)V + unit * L * ROWB;
 
     // Q'^T operands: column lr (query), contraction slice 32 ks + 8 lq; padding queries are zero
+    // Which 8 channels lane group lq contracts in step ks is free as long as Q' and K' agree.  16-bit K': 32 ks + 8 lq
+    // (a step's 32 channels are contiguous: 64 bytes per row and load).  Codes: every lane fetches 16 bytes of its
+    // row at once - 16 codes = steps 2h, 2h+1 (8 bits) or 32 codes = all four steps (4 bits) - so that a load still
+    // covers 64 contiguous bytes per row; with 8- or 4-byte loads the kernel was bound by the number of rows a load
+    // instruction touches, not by bytes.
+    auto chan0 = [&](int ks) -> int {
+        return QB == 0 ? ks * 32 + lq * 8 : (QB == 8 ? 16 * lq + 64 * (ks / 2) + 8 * (ks % 2) : 32 * lq + 8 * ks);
+    };
     vec8 qop[KS];
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks)
-        qop[ks] = (lr < R) ? *(const vec8*)(Qu + lr * D + ks * 32 + lq * 8) : zero_vec<vec8>();
+        qop[ks] = (lr < R) ? *(const vec8*)(Qu + lr * D + chan0(ks)) : zero_vec<vec8>();
 
     f32x4_t acc_o[DCH];
 #pragma unroll
@@ -173,6 +190,7 @@ __global__ __launch_bounds__(kDecThreads, FEDRAG_DEC_OCC) void decode_attn_kerne
     // per-lane byte offsets inside a 32-key tile (the tile base is wave-uniform)
     constexpr int EB = QB ? QB : 16;  // bits per stored element
     const uint32_t koff = (uint32_t)(lr * ROWB + lq * EB);          // 8 elements per lane and contraction step
+    const uint32_t kqoff = (uint32_t)(lr * ROWB + lq * 16);         // codes: 16 bytes per lane
     const uint32_t voff = (uint32_t)(lq * 4 * ROWB + lr * DCH * EB / 8);
 
     // Streaming loads go through buffer resources based at the split's first key: the address is
@@ -192,15 +210,18 @@ __global__ __launch_bounds__(kDecThreads, FEDRAG_DEC_OCC) void decode_attn_kerne
         const int soff = tile * TILEB;
 #pragma unroll
         for (int mt = 0; mt < 2; ++mt) {
+            if constexpr (QB == 0) {
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-                const int off = (int)koff + mt * 16 * ROWB + ks * 4 * EB;
-                if constexpr (QB == 0)
+                for (int ks = 0; ks < KS; ++ks) {
+                    const int off = (int)koff + mt * 16 * ROWB + ks * 4 * EB;
                     t.k[mt][ks] = __builtin_bit_cast(vec8, __builtin_amdgcn_raw_buffer_load_b128(rk, off, soff, AUX));
-                else if constexpr (QB == 8)
-                    t.kc[mt][ks] = __builtin_amdgcn_raw_buffer_load_b64(rk, off, soff, AUX);
-                else
-                    t.kc[mt][ks] = __builtin_amdgcn_raw_buffer_load_b32(rk, off, soff, AUX);
+                }
+            } else if constexpr (QB == 8) {
+#pragma unroll
+                for (int h = 0; h < KS / 2; ++h)
+                    t.kc[mt][h] = __builtin_amdgcn_raw_buffer_load_b128(rk, (int)kqoff + mt * 16 * ROWB + 64 * h, soff, AUX);
+            } else {
+                t.kc[mt] = __builtin_amdgcn_raw_buffer_load_b128(rk, (int)kqoff + mt * 16 * ROWB, soff, AUX);
             }
             if constexpr (QB != 0)
                 t.kp[mt] = __builtin_amdgcn_raw_buffer_load_b64(rkp, (mt * 16 + lr) * 8, tile * kDecTile * 8, 0);
@@ -230,12 +251,14 @@ __global__ __launch_bounds__(kDecThreads, FEDRAG_DEC_OCC) void decode_attn_kerne
         for (int mt = 0; mt < 2; ++mt) {
             int64_t key = key0 + mt * 16 + lr;
             if (key >= L) key = L - 1;
+            if constexpr (QB == 0) {
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-                const char* p = Kb + key * ROWB + ks * 4 * EB + lq * EB;
-                if constexpr (QB == 0) t.k[mt][ks] = *(const vec8*)p;
-                else if constexpr (QB == 8) t.kc[mt][ks] = *(const u32x2_t*)p;
-                else t.kc[mt][ks] = *(const uint32_t*)p;
+                for (int ks = 0; ks < KS; ++ks) t.k[mt][ks] = *(const vec8*)(Kb + key * ROWB + ks * 4 * EB + lq * EB);
+            } else if constexpr (QB == 8) {
+#pragma unroll
+                for (int h = 0; h < KS / 2; ++h) t.kc[mt][h] = *(const u32x4_t*)(Kb + key * ROWB + lq * 16 + 64 * h);
+            } else {
+                t.kc[mt] = *(const u32x4_t*)(Kb + key * ROWB + lq * 16);
             }
             if constexpr (QB != 0) t.kp[mt] = *(const u32x2_t*)(Kprm + (unit * L + key) * 2);
         }
@@ -267,7 +290,17 @@ __global__ __launch_bounds__(kDecThreads, FEDRAG_DEC_OCC) void decode_attn_kerne
             for (int ks = 0; ks < KS; ++ks) {
                 vec8 kop;
                 if constexpr (QB == 0) kop = t.k[mt][ks];
-                else kop = dequant8<T>(t.kc[mt][ks], t.kp[mt]);
+                else if constexpr (QB == 8) {
+                    const u32x4_t w = t.kc[mt][ks / 2];
+                    u32x2_t c;  // (vector elements are copied out one by one before use)
+                    const uint32_t c0 = w[2 * (ks % 2)], c1 = w[2 * (ks % 2) + 1];
+                    c[0] = c0;
+                    c[1] = c1;
+                    kop = dequant8<T>(c, t.kp[mt]);
+                } else {
+                    const uint32_t c = t.kc[mt][ks];
+                    kop = dequant8<T>(c, t.kp[mt]);
+                }
                 s[mt] = T::mfma16(kop, qop[ks], s[mt]);
             }
         }

@@ -166,12 +166,15 @@ def test_partial_attn_on_codes(oracle, case, bits):
     Vh = torch.from_numpy(oracle.dequantize_rows(vc, vp, bits)).to(dtype)
     Or, lr = oracle.partial_attn(Qs, Kh, Vh)
     PT.check_attn(O, lse, Or, lr, dtype, name)
-    # and the library's own two calls one after the other give the same bits as the fused call
+    # and the library's own two calls one after the other consume the same reconstructed elements; the fused call
+    # contracts the channels of the first product in another order (fp32 sums of exact products), nothing else
     Kd = fb.fedrag_dequantize_rows(t(kc), t(kp), bits, dtype)
     Vd = fb.fedrag_dequantize_rows(t(vc), t(vp), bits, dtype)
     O2, lse2 = fb.fedrag_partial_attn(Qs.to(DEV), Kd, Vd)
     torch.cuda.synchronize()
-    assert torch.equal(O, O2) and torch.equal(lse, lse2)
+    do, dl = float((O - O2).abs().max()), float((lse - lse2).abs().max())
+    print(f"{name} {bits} bits: fused vs two calls: O {do:.2e} lse {dl:.2e}")
+    assert do <= 1e-3 and dl <= 1e-4
 
 
 def test_partial_attn_on_codes_rejects_other_shapes():
