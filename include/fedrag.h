@@ -286,7 +286,8 @@ fedrag_status fedrag_scramble_kv_structured_quantized(const fedrag_shape* shape,
  * fedrag_partial_attn on K', V' as they arrive through the transport codec (Section 7.5): the Compute Node reads
  * the codes and dequantises them on the fly, so only d * bits / 8 + 8 bytes per key row are read instead of 2 d.
  * Every element is reconstructed exactly as fedrag_dequantize_rows would (fp32 fma, one narrowing to the storage
- * type), so the result equals fedrag_partial_attn(fedrag_dequantize_rows(...)) bit for bit.
+ * type), so the call works on the same values as fedrag_partial_attn(fedrag_dequantize_rows(...)); the two results
+ * differ only by the order in which the channels of <q, k> are summed in fp32 (a few 1e-6).
  * Qs : [B,Hq,L_q,d] storage type (16-bit);  K_codes, V_codes : uint8 [B,Hkv,L_kv,d*bits/8];
  * K_params, V_params : fp32 [B,Hkv,L_kv,2] (8-byte aligned).  bits in {8, 4}.
  * Only the decode shape is served: d_head = 128 and (n_q_heads / n_kv_heads) * L_q <= 16; anything else returns
