@@ -355,3 +355,14 @@ def test_unscramble_merge_validation(lib):
     assert f(*a) == fb.ERR_ALIAS
     a = base(); a[9] = P(7 * A + 2)    # misaligned
     assert f(*a) == fb.ERR_ALIAS
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """This build runs on one GPU: bench.py --gpus N with N > 1 exits with a message that says so (no GPU needed)."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode != 0
+    assert "one GPU" in r.stderr
