@@ -73,3 +73,21 @@ def test_workspace_too_small_is_refused():
     with pytest.raises(fb.FedragError) as e:
         fb.fedrag_partial_attn_shards(Q.to(DEV), [k.to(DEV) for k in Ks], [v.to(DEV) for v in Vs], workspace=ws)
     assert e.value.status == fb.ERR_WORKSPACE
+
+
+def test_two_compute_nodes_compose(oracle):
+    """Section 5.4: when every node supplies tokens the Compute Node role is given to two nodes, each holding the
+    shards of some Context Owners; the Inquirer aggregates their two results.  Two calls on disjoint shard sets
+    followed by fedrag_lse_merge equal one call on all shards (to rounding) and the oracle's attention over all keys."""
+    B, Hq, Hkv, d, Lq, Ls, dt = 2, 8, 2, 128, 1, [700, 1300, 512, 2049], "bf16"
+    dtype, Q, Ks, Vs = make(B, Hq, Hkv, d, Lq, Ls, dt, seed=91)
+    Qd = Q.to(DEV)
+    Kd, Vd = [k.to(DEV) for k in Ks], [v.to(DEV) for v in Vs]
+    Oa, la = fb.fedrag_partial_attn_shards(Qd, Kd[:2], Vd[:2])       # first Compute Node
+    Ob, lb = fb.fedrag_partial_attn_shards(Qd, Kd[2:], Vd[2:])       # second Compute Node
+    O2, l2 = fb.fedrag_lse_merge(torch.stack([Oa, Ob]), torch.stack([la, lb]), n_kv_heads=Hkv)
+    O1, l1 = fb.fedrag_partial_attn_shards(Qd, Kd, Vd)
+    torch.cuda.synchronize()
+    assert float((O1 - O2).abs().max()) <= 1e-5 and float((l1 - l2).abs().max()) <= 1e-5
+    Oc, lc = oracle.partial_attn(Q, torch.cat(Ks, dim=2), torch.cat(Vs, dim=2))
+    PT.check_attn(O2, l2, Oc, lc, dtype, "two compute nodes")
