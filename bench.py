@@ -279,9 +279,16 @@ def mixed_leg(torch, W, fb, dev, steps, warmup):
             for s_ in range(S):
                 fb.fedrag_partial_attn(Q, KV[s_][0], KV[s_][1], None, O_part=O[s_], lse=lse[s_], workspace=ws)
             fb.fedrag_lse_merge(O, lse, O_out=Om, lse_out=lm)
-        return run
+        need1 = fb.fedrag_partial_attn_shards_workspace_bytes(cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, d, dt, cfg.L_q,
+                                                              [cfg.L_kv] * S)
+        ws1 = torch.empty(max(need1, 16), dtype=torch.uint8, device=dev)
 
-    run_d, run_p = part(cd), part(cp)
+        def run_one_call():
+            fb.fedrag_partial_attn_shards(Q, [kv[0] for kv in KV], [kv[1] for kv in KV], None, O=Om, lse=lm,
+                                          workspace=ws1)
+        return run, run_one_call
+
+    (run_d, run_d1), (run_p, run_p1) = part(cd), part(cp)
     s_d, s_p = torch.cuda.Stream(), torch.cuda.Stream()   # default priority, both
 
     def timed(fn):
@@ -301,6 +308,7 @@ def mixed_leg(torch, W, fb, dev, steps, warmup):
             run_d()
 
     ms_d, ms_p, ms_b = timed(run_d), timed(run_p), timed(both)
+    ms_d1, ms_p1 = timed(run_d1), timed(run_p1)
     byts = 4.0 * d * cd.batch * cd.n_kv_heads * cd.L_kv * S              # K' + V', 16-bit, read once per KV head
     flop = 4.0 * cp.L_q * cp.L_kv * S * d * cp.n_q_heads * cp.batch
     return {"workload": "mixed70b: Hq64 Hkv8 d128, 8 shards x 8192 tokens, bf16; 32 decode sequences + one 4096-token "
@@ -309,6 +317,10 @@ def mixed_leg(torch, W, fb, dev, steps, warmup):
                        "frac_hbm": round(byts / ms_d / 1e6 / HBM_PEAK_GBS, 4)},
             "prefill": {"ms": round(ms_p, 4), "TFLOP/s": round(flop / ms_p / 1e9, 1),
                         "frac_mfma": round(flop / ms_p / 1e9 / MFMA_BF16_PEAK_TFLOPS, 4)},
+            "decode_one_call": {"ms": round(ms_d1, 4), "GB/s": round(byts / ms_d1 / 1e6, 1),
+                                "frac_hbm": round(byts / ms_d1 / 1e6 / HBM_PEAK_GBS, 4)},
+            "prefill_one_call": {"ms": round(ms_p1, 4), "TFLOP/s": round(flop / ms_p1 / 1e9, 1),
+                                 "frac_mfma": round(flop / ms_p1 / 1e9 / MFMA_BF16_PEAK_TFLOPS, 4)},
             "both_on_two_streams_ms": round(ms_b, 4), "sum_ms": round(ms_d + ms_p, 4),
             "max_ms": round(max(ms_d, ms_p), 4)}
 

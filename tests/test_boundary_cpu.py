@@ -333,6 +333,8 @@ def test_partial_attn_shards_validation_and_workspace(lib):
     for bad_scale in (float("nan"), 0.0):
         a = base(); a[7] = ctypes.c_float(bad_scale)
         assert f(*a) == fb.ERR_SHAPE
+    # prefill shape with enough query tiles for the chip: one run and one partial per shard
+    assert lib.fedrag_partial_attn_shards_workspace_bytes(ctypes.byref(s), 4096, n, Ls) == n * 32 * 4096 * (128 + 1) * 4
     # bad arguments report 0 bytes
     assert lib.fedrag_partial_attn_shards_workspace_bytes(ctypes.byref(s), 1, 17, Ls) == 0
     assert lib.fedrag_partial_attn_shards_workspace_bytes(ctypes.byref(s), 1, n, None) == 0

@@ -22,6 +22,8 @@ CASES = [
     ("pre_bf16", 1, 4, 2, 128, 70, [1500, 64, 0, 700], "bf16"),        # prefill kernel, runs inside the long shards
     ("pre_bf16_d64", 2, 2, 2, 64, 300, [1111, 129], "bf16"),
     ("pre_f16", 1, 2, 1, 128, 40, [100, 777], "f16"),
+    # enough query tiles to cover the chip: one run per shard
+    ("pre_bf16_walk", 4, 8, 2, 128, 1100, [200, 0, 333], "bf16"),
     ("f32", 2, 4, 2, 128, 3, [197, 0, 50], "f32"),
 ]
 
