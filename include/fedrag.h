@@ -5,7 +5,9 @@
  * General rules for every call
  * ----------------------------
  * - Every data pointer is DEVICE memory owned by the caller, 16-byte aligned, dense row-major.
- *   The library never allocates, frees or keeps a pointer after the call returns.
+ *   The library never allocates, frees or keeps a pointer after the call returns.  Two kinds of argument are HOST
+ *   memory and say so where they are declared: the fedrag_structured_key structs (which hold device pointers) and
+ *   the per-shard arrays of fedrag_partial_attn_shards; they are read during the call only.
  * - Tensors are laid out [batch, heads, tokens, d_head] ("[B,H,L,d]").  Query head h uses KV head
  *   h / (n_q_heads / n_kv_heads); scrambling matrices are per KV head, [n_kv_heads, d, d], row-major,
  *   and multiply ROW vectors from the right (x . Phi), the paper's convention (Section 2.1, footnote).
