@@ -694,28 +694,32 @@ def main():
     if args.no_prefill:
         want -= {"rerank", "local_attn", "request", "mixed70b", "prefill", "long_decode"}
     half = max(5, args.steps // 2)
-    if "shards" in want:
-        line["shards"] = shards_leg(torch, fb, g, args.steps, args.warmup)
-    if "codec" in want:
-        line["codec"] = codec_leg(torch, fb, g, args.steps, args.warmup)
-    if "structured" in want:
-        line["structured"] = structured_leg(torch, W, fb, g, dev, args.steps, args.warmup)
-    if "rerank" in want:
-        line["rerank"] = rerank_leg(torch, W, fb, dev, half, args.warmup)
-    if "local_attn" in want:
-        line["local_attn"] = local_attn_leg(torch, W, fb, dev, half, args.warmup)
-    if "request" in want:
-        line["request"] = request_leg(torch, W, fb, dev, half, args.warmup)
-    if "mixed70b" in want:
-        line["mixed70b"] = mixed_leg(torch, W, fb, dev, half, args.warmup)
-    if "prefill" in want:
-        line["prefill"] = prefill_leg(torch, W, fb, dev, half, args.warmup)
+
+    def leg(name, fn):
+        """The extra legs must not cost the headline its JSON line: a leg that fails reports its error instead."""
+        if name not in want:
+            return
+        try:
+            line[name] = fn()
+        except Exception as e:  # noqa: BLE001 - reported in the line, the step above is already measured
+            torch.cuda.synchronize()
+            line[name] = {"error": f"{type(e).__name__}: {e}"}
+            print(f"bench.py: leg {name} failed: {e}", file=sys.stderr)
+
+    leg("shards", lambda: shards_leg(torch, fb, g, args.steps, args.warmup))
+    leg("codec", lambda: codec_leg(torch, fb, g, args.steps, args.warmup))
+    leg("structured", lambda: structured_leg(torch, W, fb, g, dev, args.steps, args.warmup))
+    leg("rerank", lambda: rerank_leg(torch, W, fb, dev, half, args.warmup))
+    leg("local_attn", lambda: local_attn_leg(torch, W, fb, dev, half, args.warmup))
+    leg("request", lambda: request_leg(torch, W, fb, dev, half, args.warmup))
+    leg("mixed70b", lambda: mixed_leg(torch, W, fb, dev, half, args.warmup))
+    leg("prefill", lambda: prefill_leg(torch, W, fb, dev, half, args.warmup))
     if not args.no_cpu:
         line["cpu_baseline"] = cpu_leg(torch, W, g, args.cpu_shards)
     if "long_decode" in want:   # last: it takes 64 GiB of device memory
         del g
         torch.cuda.empty_cache()
-        line["long_decode"] = long_decode_leg(torch, W, fb, dev, 5, args.warmup)
+        leg("long_decode", lambda: long_decode_leg(torch, W, fb, dev, 5, args.warmup))
     print(json.dumps(line))
 
 
