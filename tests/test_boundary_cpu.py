@@ -368,3 +368,25 @@ def test_bench_refuses_more_than_one_gpu():
                        timeout=120)
     assert r.returncode != 0
     assert "one GPU" in r.stderr
+
+
+def test_header_is_plain_c_and_links(tmp_path):
+    """include/fedrag.h compiles as C99 with a C compiler, and a C program linked against the library runs its
+    host-side paths (no GPU needed)."""
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no C compiler")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    from paper_2605_25716_amd import build as fbuild
+    lib_dir = os.path.dirname(fbuild.LIB_PATH)
+    exe = str(tmp_path / "abi_check")
+    cmd = [gcc, "-std=c99", "-pedantic", "-Wall", "-Werror", "-I", os.path.join(root, "include"),
+           os.path.join(root, "tests", "c", "abi_check.c"), "-o", exe, "-L", lib_dir, "-lfedrag",
+           "-Wl,-rpath," + lib_dir, "-Wl,-rpath,/opt/rocm/lib"]
+    r = subprocess.run(cmd, capture_output=True, text=True, timeout=300)
+    assert r.returncode == 0, r.stderr
+    r = subprocess.run([exe], capture_output=True, text=True, timeout=300)
+    assert r.returncode == 0, f"exit {r.returncode}: {r.stdout} {r.stderr}"
+    assert "abi ok" in r.stdout
