@@ -390,3 +390,23 @@ def test_header_is_plain_c_and_links(tmp_path):
     r = subprocess.run([exe], capture_output=True, text=True, timeout=300)
     assert r.returncode == 0, f"exit {r.returncode}: {r.stdout} {r.stderr}"
     assert "abi ok" in r.stdout
+
+
+def test_missing_library_fails_loudly(tmp_path):
+    """There is no fallback path: with no built library the binding raises instead of computing something else."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    code = (
+        "import sys; sys.path.insert(0, %r)\n"
+        "from paper_2605_25716_amd import build as b\n"
+        "b.LIB_PATH = %r\n"
+        "from paper_2605_25716_amd import binding as fb\n"
+        "try:\n"
+        "    fb.load()\n"
+        "except FileNotFoundError as e:\n"
+        "    print('raised:', e); sys.exit(0)\n"
+        "sys.exit(3)\n" % (root, str(tmp_path / "libfedrag_absent.so")))
+    r = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, timeout=300)
+    assert r.returncode == 0, r.stdout + r.stderr
+    assert "no fallback" in r.stdout
