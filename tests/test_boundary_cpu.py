@@ -410,3 +410,24 @@ def test_missing_library_fails_loudly(tmp_path):
     r = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, timeout=300)
     assert r.returncode == 0, r.stdout + r.stderr
     assert "no fallback" in r.stdout
+
+
+def test_product_and_oracle_do_not_reach_into_each_other():
+    """The HIP path and the oracle share no code: the package never imports, loads or names anything under oracle/
+    (the input generators only mention it in comments), and the oracle never names the package or its library."""
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    pkg = os.path.join(root, "paper_2605_25716_amd")
+    bad = []
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if not f.endswith((".py", ".hip", ".h")):
+                continue
+            text = open(os.path.join(dirpath, f), encoding="utf-8").read()
+            if re.search(r"^\s*(import|from)\s+oracle\b", text, re.M) or "libfedrag_oracle" in text or "oracle/" in text:
+                bad.append(os.path.join(dirpath, f))
+    for f in os.listdir(os.path.join(root, "oracle")):
+        if f.endswith((".py", ".c", ".h")):
+            text = open(os.path.join(root, "oracle", f), encoding="utf-8").read()
+            if "paper_2605_25716_amd" in text or "libfedrag.so" in text or "fedrag.h" in text:
+                bad.append(os.path.join("oracle", f))
+    assert not bad, bad
