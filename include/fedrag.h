@@ -20,7 +20,9 @@
  *   they never synchronise with the host and never copy between host and device.
  * - All argument checks happen on the host before anything is enqueued; on any error nothing is launched and
  *   no output is written.  Errors are return codes only.  FEDRAG_ERR_DEVICE reports a failed launch.
- * - Supported: d_head in {64, 128}; n_q_heads % n_kv_heads == 0; token counts >= 0 (zero is legal).
+ * - Supported: d_head in {64, 128}; n_q_heads % n_kv_heads == 0; token counts >= 0.  Zero is legal: a call whose
+ *   output has no rows returns FEDRAG_OK at once (its tensor pointers may then be NULL), and attention over no keys
+ *   writes O = 0, lse = -inf.
  * - The library draws no randomness: keys (Phi's, permutations) come from the key holders
  *   (Inquirer and Context Owner negotiate them per request, Section 5.1 / Section 6).
  *

@@ -1,0 +1,62 @@
+"""Degenerate sizes through every call on the GPU: no queries, no keys, one row.  Nothing may fault, outputs that
+exist get the documented values (O = 0, lse = -inf for attention over no keys)."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2605_25716_amd import binding as fb
+from paper_2605_25716_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+
+
+@pytest.mark.parametrize("dt", ["bf16", "f32"])
+def test_zero_queries_and_zero_keys(dt):
+    dtype = W.torch_dtype(dt)
+    B, Hq, Hkv, d = 2, 4, 2, 128
+    keys = W.make_keys(Hkv, d, 1, 8, 1, seed=5, dtype=dtype)
+    z = lambda H, L: torch.zeros((B, H, L, d), dtype=dtype, device=DEV)
+    phi = lambda n: getattr(keys, n).to(DEV)
+    # no rows at all
+    assert fb.fedrag_scramble_q(z(Hq, 0), phi("phi_q"), None).shape == (B, Hq, 0, d)
+    Ks, Vs = fb.fedrag_scramble_kv(z(Hkv, 0), z(Hkv, 0), phi("phi_k"), phi("phi_v"), None, n_q_heads=Hq)
+    assert Ks.shape == (B, Hkv, 0, d) and Vs.shape == (B, Hkv, 0, d)
+    O, lse = fb.fedrag_partial_attn(z(Hq, 0), z(Hkv, 5), z(Hkv, 5))
+    assert O.shape == (B, Hq, 0, d) and lse.shape == (B, Hq, 0)
+    # queries but no keys: the empty partial
+    for Lq in (1, 70):
+        O, lse = fb.fedrag_partial_attn(z(Hq, Lq), z(Hkv, 0), z(Hkv, 0))
+        O2, lse2 = fb.fedrag_partial_attn_shards(z(Hq, Lq), [z(Hkv, 0), z(Hkv, 0)], [z(Hkv, 0), z(Hkv, 0)])
+        torch.cuda.synchronize()
+        for o, l in ((O, lse), (O2, lse2)):
+            assert bool((o == 0).all()) and bool(torch.isneginf(l).all())
+    # the aggregation of empty partials stays empty, Dec of no rows is a no-op
+    Op = torch.zeros((3, B, Hq, 2, d), device=DEV)
+    lp = torch.full((3, B, Hq, 2), -np.inf, device=DEV)
+    Om, lm = fb.fedrag_lse_merge(Op, lp, n_kv_heads=Hkv)
+    torch.cuda.synchronize()
+    assert bool((Om == 0).all()) and bool(torch.isneginf(lm).all())
+    out = fb.fedrag_unscramble(torch.zeros((B, Hq, 0, d), device=DEV), phi("phi_v_inv"), None)
+    assert out.shape == (B, Hq, 0, d)
+    torch.cuda.synchronize()
+
+
+def test_single_row_everything():
+    """One sequence, one head, one query, one key: every kernel at its smallest non-empty size."""
+    dtype = torch.bfloat16
+    d = 64
+    keys = W.make_keys(1, d, 1, 1, 1, seed=6, dtype=dtype)
+    g = torch.Generator().manual_seed(3)
+    Q = torch.randn((1, 1, 1, d), generator=g).to(dtype).to(DEV)
+    K = torch.randn((1, 1, 1, d), generator=g).to(dtype).to(DEV)
+    V = torch.randn((1, 1, 1, d), generator=g).to(dtype).to(DEV)
+    Qs = fb.fedrag_scramble_q(Q, keys.phi_q.to(DEV), None)
+    Ks, Vs = fb.fedrag_scramble_kv(K, V, keys.phi_k.to(DEV), keys.phi_v.to(DEV), None, n_q_heads=1)
+    O, lse = fb.fedrag_partial_attn(Qs, Ks, Vs)
+    out = fb.fedrag_unscramble(O, keys.phi_v_inv.to(DEV), None)
+    torch.cuda.synchronize()
+    # one key: the output is that key's value row, whatever the score
+    assert float((O - Vs.float()).abs().max()) == 0.0
+    assert float((out - V.float()).abs().max()) <= 2e-2
+    assert np.isfinite(float(lse))
