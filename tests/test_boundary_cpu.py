@@ -431,3 +431,19 @@ def test_product_and_oracle_do_not_reach_into_each_other():
             if "paper_2605_25716_amd" in text or "libfedrag.so" in text or "fedrag.h" in text:
                 bad.append(os.path.join("oracle", f))
     assert not bad, bad
+
+
+def test_calls_without_rows_accept_null_tensors(lib):
+    """A call whose output has no rows returns FEDRAG_OK at once; its tensor pointers may be NULL."""
+    s = shape(B=2, Hq=8, Hkv=2)
+    z = ctypes.c_float(0.088)
+    assert lib.fedrag_scramble_q(ctypes.byref(s), 0, None, None, None, None, None) == fb.OK
+    assert lib.fedrag_scramble_kv(ctypes.byref(s), 0, None, None, None, None, None, 1, None, None, None) == fb.OK
+    assert lib.fedrag_partial_attn(ctypes.byref(s), 0, 100, None, None, None, z, None, None, None, 0, None) == fb.OK
+    assert lib.fedrag_local_attn(ctypes.byref(s), 0, 100, None, None, None, z, None, None, None, 0, None) == fb.OK
+    assert lib.fedrag_lse_merge(ctypes.byref(s), 0, 3, None, None, None, None, None) == fb.OK
+    assert lib.fedrag_unscramble(ctypes.byref(s), 0, None, None, None, None, None) == fb.OK
+    assert lib.fedrag_unscramble_merge(ctypes.byref(s), 0, None, None, None, None, None, None, None, None, None) == fb.OK
+    # with rows the same pointers are refused
+    assert lib.fedrag_scramble_q(ctypes.byref(s), 1, None, None, None, None, None) == fb.ERR_NULL
+    assert lib.fedrag_unscramble(ctypes.byref(s), 1, None, None, None, None, None) == fb.ERR_NULL
