@@ -458,6 +458,22 @@ def long_decode_leg(torch, W, fb, dev, steps, warmup):
         fb.fedrag_lse_merge(Op, lp, n_kv_heads=Hkv, O_out=O, lse_out=lse)
 
     out = {"workload": "long_decode: B64 Hq32 Hkv8 d128 Lq1, 8 shards x 32768 tokens, bf16 (64 GiB of K', V')"}
+    # Enc of one shard at this size (8 GiB read, 8 GiB written), into a spare pair of buffers
+    keys = W.make_keys(Hkv, d, 1, L, 1, seed=cfg.seed, dtype=dt)
+    phi_k, phi_v, perm = keys.phi_k.to(dev), keys.phi_v.to(dev), keys.perm_kv[0].to(dev)
+    Ko, Vo = torch.empty_like(Ks[0]), torch.empty_like(Vs[0])
+    enc = lambda: fb.fedrag_scramble_kv(Ks[0], Vs[0], phi_k, phi_v, perm, n_q_heads=Hq, K_out=Ko, V_out=Vo)
+    enc()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(3):
+        enc()
+    torch.cuda.synchronize()
+    ms = 1e3 * (time.perf_counter() - t0) / 3
+    enc_bytes = 8.0 * d * B * Hkv * L
+    out["scramble_kv_one_shard"] = {"ms": round(ms, 3), "GB/s": round(enc_bytes / ms / 1e6, 1),
+                                    "frac_hbm": round(enc_bytes / ms / 1e6 / HBM_PEAK_GBS, 4)}
+    del Ko, Vo
     byts = 4.0 * d * B * Hkv * L * S
     for name, fn in (("one_call", one_call), ("shard_by_shard", per_shard)):
         for _ in range(max(1, warmup // 2)):
