@@ -20,9 +20,9 @@
  *   they never synchronise with the host and never copy between host and device.
  * - All argument checks happen on the host before anything is enqueued; on any error nothing is launched and
  *   no output is written.  Errors are return codes only.  FEDRAG_ERR_DEVICE reports a failed launch.
- * - Supported: d_head in {64, 128}; n_q_heads % n_kv_heads == 0; token counts >= 0.  Zero is legal: a call whose
- *   output has no rows returns FEDRAG_OK at once (its tensor pointers may then be NULL), and attention over no keys
- *   writes O = 0, lse = -inf.
+ * - Supported: d_head in {64, 128}; n_q_heads % n_kv_heads == 0; batch and token counts >= 0.  Zero is legal: a call
+ *   whose output has no rows (no sequences, or no tokens) returns FEDRAG_OK at once (its tensor pointers may then be
+ *   NULL), and attention over no keys writes O = 0, lse = -inf.
  * - The library draws no randomness: keys (Phi's, permutations) come from the key holders
  *   (Inquirer and Context Owner negotiate them per request, Section 5.1 / Section 6).
  *
@@ -105,6 +105,9 @@ fedrag_status fedrag_partial_attn(const fedrag_shape* shape, int64_t L_q, int64_
                                   float* O_part, float* lse,
                                   void* workspace, size_t workspace_bytes, void* stream);
 
+/* Bytes of workspace fedrag_partial_attn (and the calls that refer to it) needs for these sizes; 0 for arguments the
+ * call would reject.  The key runs are planned for the compute-unit count of the device that is current in the
+ * calling thread (256 when there is none), so ask with the device current on which the call will run. */
 size_t fedrag_partial_attn_workspace_bytes(const fedrag_shape* shape, int64_t L_q, int64_t L_kv);
 
 /*

@@ -96,7 +96,8 @@ def load() -> ctypes.CDLL:
         lib.fedrag_status_string.argtypes = [ctypes.c_int]
         lib.fedrag_status_string.restype = ctypes.c_char_p
         lib.fedrag_version.restype = ctypes.c_int
-        for name in ("fedrag_scramble_kv", "fedrag_scramble_q", "fedrag_partial_attn", "fedrag_lse_merge",
+        for name in ("fedrag_scramble_kv", "fedrag_scramble_q", "fedrag_partial_attn",
+                     "fedrag_partial_attn_shards", "fedrag_unscramble_merge", "fedrag_lse_merge",
                      "fedrag_unscramble", "fedrag_invert_perm", "fedrag_scramble_kv_structured",
                      "fedrag_scramble_q_structured", "fedrag_unscramble_structured", "fedrag_local_attn",
                      "fedrag_unpermute_lse", "fedrag_partial_attn_varlen", "fedrag_quantize_rows",

@@ -8,6 +8,7 @@
 #include "fedrag_device.h"
 #include "fedrag_host.h"
 
+#include <atomic>
 #include <climits>
 #include <cstdint>
 
@@ -100,17 +101,24 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const float* __restrict__
 // attribute query is host-only and falls back to that number when no device is present.
 #ifndef FEDRAG_DEC_WGS
 static int decode_target_wgs() {
-    static int cached = 0;
-    if (cached == 0) {
-        int dev = 0, n = 0;
-        if (hipGetDevice(&dev) == hipSuccess &&
-            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
-            cached = n;
-        else
-            cached = 256;
+    // the count belongs to the device that is current in the calling thread; it is cached per device ordinal in
+    // atomics, so concurrent first calls only repeat the query
+    constexpr int kMaxDev = 64;
+    static std::atomic<int> cached[kMaxDev];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDev) {
         (void)hipGetLastError();
+        return 256;
     }
-    return cached;
+    int n = cached[dev].load(std::memory_order_relaxed);
+    if (n == 0) {
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) {
+            (void)hipGetLastError();
+            return 256;
+        }
+        cached[dev].store(n, std::memory_order_relaxed);
+    }
+    return n;
 }
 #define FEDRAG_DEC_WGS decode_target_wgs()
 #endif
@@ -186,6 +194,12 @@ KeyRuns attn_runs_of(const AttnProblem& p) {
         KeyRuns r = attn_plan_runs(p.B, p.Hq, p.Hkv, p.dtype, p.Lq, 1, &p.Lkv);
         r.K[0] = p.K;
         r.V[0] = p.V;
+        if (p.single_run && r.n_runs > 1) {  // all keys of the shard in one run (a whole number of key tiles)
+            const int64_t q = use_decode_kernel(p.Hq, p.Hkv, p.Lq) ? kDecStride : kPreK;
+            r.per[0] = ((r.L[0] + q - 1) / q) * q;
+            r.first[1] = 1;
+            r.n_runs = 1;
+        }
         return r;
     }
     KeyRuns r = attn_plan_runs(p.B, p.Hq, p.Hkv, p.dtype, p.Lq, p.n_shards, p.Ls);
@@ -250,6 +264,9 @@ hipError_t launch_partial_attn(const AttnProblem& p_in, hipStream_t stream) {
                 one.K = p.Ks[idx[j]];
                 one.V = p.Vs[idx[j]];
                 one.Lkv = p.Ls[idx[j]];
+                one.single_run = true;  // the workspace holds the per-shard partials: no runs inside a shard
+                one.workspace = nullptr;
+                one.workspace_bytes = 0;
                 one.O = Ow + (size_t)j * rows * p.D;
                 one.lse = Lw + (size_t)j * rows;
                 const hipError_t e = launch_partial_attn(one, stream);

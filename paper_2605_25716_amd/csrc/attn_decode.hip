@@ -112,7 +112,9 @@ __global__ __launch_bounds__(kDecThreads, FEDRAG_DEC_OCC) void decode_attn_kerne
                                                                      const float* __restrict__ Vprm, int R,
                                                                      float scale_log2, float* __restrict__ O,
                                                                      float* __restrict__ lse, int64_t total_rows,
-                                                                     const int32_t* __restrict__ kv_lens, int Hkv) {
+                                                                     const int32_t* __restrict__ kv_lens,
+                                                                     const int32_t* __restrict__ q_lens, int Lq,
+                                                                     int Hkv) {
     typedef typename T::elem elem;
     typedef typename T::vec8 vec8;
     typedef DecTile<T, D, QB> Tile;
@@ -246,11 +248,14 @@ __global__ __launch_bounds__(kDecThreads, FEDRAG_DEC_OCC) void decode_attn_kerne
             }
         }
     };
-    auto load_clamped = [&](int64_t key0, Tile& t) {  // ragged last tile: rows past the end re-read row L-1
+    // ragged last tile: rows past the end of the run re-read its last key, k_end - 1 (the tail exists, so
+    // k_end > k_begin).  Rows past k_end are never touched: with per-sequence key counts they are padding that may
+    // hold anything, and a NaN there would survive the multiplication by a zero probability.
+    auto load_clamped = [&](int64_t key0, Tile& t) {
 #pragma unroll
         for (int mt = 0; mt < 2; ++mt) {
             int64_t key = key0 + mt * 16 + lr;
-            if (key >= L) key = L - 1;
+            if (key >= k_end) key = k_end - 1;
             if constexpr (QB == 0) {
 #pragma unroll
                 for (int ks = 0; ks < KS; ++ks) t.k[mt][ks] = *(const vec8*)(Kb + key * ROWB + ks * 4 * EB + lq * EB);
@@ -265,7 +270,7 @@ __global__ __launch_bounds__(kDecThreads, FEDRAG_DEC_OCC) void decode_attn_kerne
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
             int64_t key = key0 + (e / 4) * 16 + lq * 4 + (e % 4);
-            if (key >= L) key = L - 1;
+            if (key >= k_end) key = k_end - 1;
             const char* p = Vb + key * ROWB + lr * DCH * EB / 8;
             if constexpr (QB == 0) {
 #pragma unroll
@@ -410,9 +415,17 @@ __global__ __launch_bounds__(kDecThreads, FEDRAG_DEC_OCC) void decode_attn_kerne
     __syncthreads();
     float* Oout = O + ((int64_t)run * total_rows + unit * R) * D;
     float* Lout = lse + (int64_t)run * total_rows + unit * R;
+    // padded batch with per-sequence query counts: row n of the unit is query n % Lq of its head; rows past the
+    // sequence's count are padding and are not written
+    int q_rows = Lq;
+    if (q_lens) {
+        const int v = q_lens[unit / Hkv];
+        q_rows = v < 0 ? 0 : (v < Lq ? v : Lq);
+    }
     for (int idx = tid; idx < R * D; idx += kDecThreads) {
         const int n = idx / D;
         const int d = idx % D;
+        if (n % Lq >= q_rows) continue;
         float M = sm_m[0][n];
 #pragma unroll
         for (int w = 1; w < kDecWaves; ++w) M = fmaxf(M, sm_m[w][n]);
@@ -438,6 +451,8 @@ static hipError_t launch_decode_t(const AttnProblem& p, hipStream_t stream) {
     const int splits = runs.n_runs;
     if (splits < 1) return hipErrorInvalidValue;
     if (QB != 0 && p.n_shards > 1) return hipErrorInvalidValue;
+    for (int i = 0; i < kMaxShards; ++i)  // a run is addressed with 32-bit byte offsets
+        if (runs.L[i] > 0 && runs.per[i] * (int64_t)(QB ? D * QB / 8 : D * 2) > 0x7fffffffLL) return hipErrorInvalidValue;
     const int R = (int)((p.Hq / p.Hkv) * p.Lq);
     const int64_t units = (int64_t)p.B * p.Hkv;
     float* Odst = p.O;
@@ -449,10 +464,10 @@ static hipError_t launch_decode_t(const AttnProblem& p, hipStream_t stream) {
     }
     hipLaunchKernelGGL((decode_attn_kernel<T, D, QB>), dim3((unsigned)(units * splits)), dim3(kDecThreads), 0, stream,
                        (const elem*)p.Q, runs, p.K_params, p.V_params, R, scale_log2, Odst, Ldst, rows, p.kv_lens,
-                       p.Hkv);
+                       p.q_lens, (int)p.Lq, p.Hkv);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || splits == 1) return e;
-    return launch_lse_merge(Odst, Ldst, splits, rows, D, p.O, p.lse, stream);
+    return launch_lse_merge(Odst, Ldst, splits, rows, D, p.O, p.lse, stream, p.q_lens, p.Lq, (int64_t)p.Hq * p.Lq);
 }
 
 hipError_t launch_decode_attn(const AttnProblem& p, hipStream_t stream) {

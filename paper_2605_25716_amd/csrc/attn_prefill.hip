@@ -37,7 +37,11 @@ __device__ __forceinline__ u32x2_t lds_read_tr16(const char* p) {
 }
 
 // CAUSAL: the queries are the last Lq of the L tokens whose K'/V' are given, and query i sees keys 0 .. i + (L - Lq)
-// (Section 5.3: the Inquirer's own part of a decoder layer's attention).
+// (Section 5.3: the Inquirer's own part of a decoder layer's attention).  That call works on plaintext V, whose
+// outlier channels are not spread by a scrambling matrix (|v| of several tens), so a probability rounded once to the
+// storage type (relative error 2^-9 in bf16) would move an output by more than the 16-bit output tolerance.  The
+// CAUSAL instantiation therefore feeds the second product P = P_hi + P_lo, two storage-type terms (about 16
+// significant bits), at the price of twice the MFMAs of that product.
 template <class T, int D, bool CAUSAL>
 __global__ __launch_bounds__(kPreThreads, 1) void prefill_attn_kernel(const typename T::elem* __restrict__ Q,
                                                                       const KeyRuns runs, int Hq, int Hkv, int64_t Lq,
@@ -200,6 +204,13 @@ __global__ __launch_bounds__(kPreThreads, 1) void prefill_attn_kernel(const type
     f32x16_t S0;      // S^T of the current tile, keys 0..31
     f32x16_t S1[2];   // S1[t & 1]: S^T of tile t, keys 32..63 (kept one iteration longer, see below)
     vec8 P[2][4];     // P[t & 1]: P^T operands of tile t, one per 16-key step
+    constexpr bool SPLIT = CAUSAL;           // second storage-type term of every probability (see above)
+    vec8 Plo[SPLIT ? 2 : 1][SPLIT ? 4 : 1];  // Plo[t & 1]: P - P as stored in P[t & 1], narrowed
+    auto put_p = [&](int par, int kk, int e, float pe) {
+        const elem hi = T::from_float(pe);
+        P[par][kk][e] = hi;
+        if constexpr (SPLIT) Plo[par][kk][e] = T::from_float(pe - T::to_float(hi));
+    };
     float alph[2];    // alph[t & 1]: rescale factor of the running output that goes with P(t)
 
     auto read_vop = [&](const char* vt, int kk, int i) -> vec8 {
@@ -252,7 +263,7 @@ __global__ __launch_bounds__(kPreThreads, 1) void prefill_attn_kernel(const type
                 for (int r = r0; r < r1; ++r) {
                     const float pe = fast_exp2(__builtin_fmaf(S1[q][r], scale_log2, -m_run));
                     psum += pe;
-                    P[q][2 + r / 8][r % 8] = T::from_float(pe);
+                    put_p(q, 2 + r / 8, r % 8, pe);
                 }
                 pin_here(psum);  // the slice's vector work stays in the slice
                 __builtin_amdgcn_sched_barrier(0);
@@ -265,7 +276,7 @@ __global__ __launch_bounds__(kPreThreads, 1) void prefill_attn_kernel(const type
                 for (int r = 0; r < 16; ++r) {
                     const float pe = fast_exp2(__builtin_fmaf(S1[q][r], scale_log2, -m_run));
                     psum += pe;
-                    P[q][2 + r / 8][r % 8] = T::from_float(pe);
+                    put_p(q, 2 + r / 8, r % 8, pe);
                 }
                 l_run += psum;
             }
@@ -304,6 +315,7 @@ __global__ __launch_bounds__(kPreThreads, 1) void prefill_attn_kernel(const type
             for (int j = 0; j < NM; ++j) {
                 if (j + kPrePD < NM) vop[j + kPrePD] = read_vop(vt, (j + kPrePD) / MT, (j + kPrePD) % MT);
                 acc_o[j % MT] = T::mfma32(vop[j], P[q][j / MT], acc_o[j % MT]);
+                if constexpr (SPLIT) acc_o[j % MT] = T::mfma32(vop[j], Plo[q][j / MT], acc_o[j % MT]);
                 if (j == 0) {
 #pragma unroll
                     for (int r = 1; r < 16; ++r) mx = fmaxf(mx, S0[r]);
@@ -324,7 +336,7 @@ __global__ __launch_bounds__(kPreThreads, 1) void prefill_attn_kernel(const type
                     for (int r = r0; r < r1; ++r) {
                         const float pe = fast_exp2(__builtin_fmaf(S0[r], scale_log2, -m_new));
                         psum += pe;
-                        P[p][r / 8][r % 8] = T::from_float(pe);
+                        put_p(p, r / 8, r % 8, pe);
                     }
                 }
                 __builtin_amdgcn_sched_barrier(0);
@@ -336,7 +348,11 @@ __global__ __launch_bounds__(kPreThreads, 1) void prefill_attn_kernel(const type
 #pragma unroll
                 for (int kk = 0; kk < 4; ++kk)
 #pragma unroll
-                    for (int i = 0; i < MT; ++i) acc_o[i] = T::mfma32(read_vop(vt, kk, i), P[q][kk], acc_o[i]);
+                    for (int i = 0; i < MT; ++i) {
+                        const vec8 vop = read_vop(vt, kk, i);
+                        acc_o[i] = T::mfma32(vop, P[q][kk], acc_o[i]);
+                        if constexpr (SPLIT) acc_o[i] = T::mfma32(vop, Plo[q][kk], acc_o[i]);
+                    }
             }
             if (doAB) {  // B1(t); keys past the end of the shard get a score of -inf (also seen by B2(t) later)
                 const int key0 = t * kPreK;
@@ -359,7 +375,7 @@ __global__ __launch_bounds__(kPreThreads, 1) void prefill_attn_kernel(const type
                 for (int r = 0; r < 16; ++r) {
                     const float pe = fast_exp2(__builtin_fmaf(S0[r], scale_log2, -m_new));
                     psum += pe;
-                    P[p][r / 8][r % 8] = T::from_float(pe);
+                    put_p(p, r / 8, r % 8, pe);
                 }
                 l_run = l_run * alph[p] + psum;
                 m_run = m_new;
@@ -371,6 +387,11 @@ __global__ __launch_bounds__(kPreThreads, 1) void prefill_attn_kernel(const type
             u32x4_t w = __builtin_bit_cast(u32x4_t, P[p][kk]);
             pin_here(w);
             P[p][kk] = __builtin_bit_cast(vec8, w);
+            if constexpr (SPLIT) {
+                u32x4_t wl = __builtin_bit_cast(u32x4_t, Plo[p][kk]);
+                pin_here(wl);
+                Plo[p][kk] = __builtin_bit_cast(vec8, wl);
+            }
         }
         pin_here(l_run);
         __builtin_amdgcn_sched_barrier(0);

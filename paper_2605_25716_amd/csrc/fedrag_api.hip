@@ -66,7 +66,7 @@ fedrag_status fedrag_scramble_kv(const fedrag_shape* shape, int64_t L_kv, const 
     fedrag_status st = check_shape(shape, true);
     if (st != FEDRAG_OK) return st;
     if (L_kv < 0 || L_kv > INT32_MAX) return FEDRAG_ERR_SHAPE;  // gather indices are int32
-    if (L_kv == 0) return FEDRAG_OK;  // nothing to do: the tensors have no rows and their pointers may be NULL
+    if (L_kv == 0 || shape->batch == 0) return FEDRAG_OK;  // no rows: nothing to do, tensor pointers may be NULL
     if (!K || !V || !phi_k || !phi_v || !K_out || !V_out) return FEDRAG_ERR_NULL;
     if (perm_kv && n_perm != 1 && n_perm != shape->batch) return FEDRAG_ERR_SHAPE;
     int64_t n;
@@ -99,7 +99,7 @@ fedrag_status fedrag_scramble_q(const fedrag_shape* shape, int64_t L_q, const vo
     fedrag_status st = check_shape(shape, true);
     if (st != FEDRAG_OK) return st;
     if (L_q < 0 || L_q > INT32_MAX) return FEDRAG_ERR_SHAPE;
-    if (L_q == 0) return FEDRAG_OK;  // nothing to do: the tensors have no rows and their pointers may be NULL
+    if (L_q == 0 || shape->batch == 0) return FEDRAG_OK;  // no rows: nothing to do, tensor pointers may be NULL
     if (!Q || !phi_q || !Q_out) return FEDRAG_ERR_NULL;
     int64_t n;
     if (!tensor_elems(shape->batch, shape->n_q_heads, L_q, shape->d_head, &n)) return FEDRAG_ERR_SHAPE;
@@ -135,7 +135,7 @@ fedrag_status fedrag_partial_attn(const fedrag_shape* shape, int64_t L_q, int64_
     fedrag_status st = check_shape(shape, true);
     if (st != FEDRAG_OK) return st;
     if (L_q < 0 || L_kv < 0 || L_q > INT32_MAX || L_kv > INT32_MAX) return FEDRAG_ERR_SHAPE;
-    if (L_q == 0) return FEDRAG_OK;  // nothing to do: the tensors have no rows and their pointers may be NULL
+    if (L_q == 0 || shape->batch == 0) return FEDRAG_OK;  // no rows: nothing to do, tensor pointers may be NULL
     if (!Qs || !O_part || !lse) return FEDRAG_ERR_NULL;
     if (L_kv > 0 && (!Ks || !Vs)) return FEDRAG_ERR_NULL;
     int64_t nq, nk;
@@ -176,7 +176,7 @@ fedrag_status fedrag_partial_attn_shards(const fedrag_shape* shape, int64_t L_q,
     fedrag_status st = check_shape(shape, true);
     if (st != FEDRAG_OK) return st;
     if (n_shards < 1 || n_shards > kMaxShards) return FEDRAG_ERR_SHAPE;
-    if (L_q == 0) return FEDRAG_OK;  // nothing to do: the tensors have no rows and their pointers may be NULL
+    if (L_q == 0 || shape->batch == 0) return FEDRAG_OK;  // no rows: nothing to do, tensor pointers may be NULL
     if (!L_kv || !Ks || !Vs || !Qs || !O || !lse) return FEDRAG_ERR_NULL;
     if (L_q < 0 || L_q > INT32_MAX) return FEDRAG_ERR_SHAPE;
     int64_t nq, nk;
@@ -217,7 +217,7 @@ fedrag_status fedrag_partial_attn_varlen(const fedrag_shape* shape, int64_t L_q,
     fedrag_status st = check_shape(shape, true);
     if (st != FEDRAG_OK) return st;
     if (L_q < 0 || L_kv < 0 || L_q > INT32_MAX || L_kv > INT32_MAX) return FEDRAG_ERR_SHAPE;
-    if (L_q == 0) return FEDRAG_OK;  // nothing to do: the tensors have no rows and their pointers may be NULL
+    if (L_q == 0 || shape->batch == 0) return FEDRAG_OK;  // no rows: nothing to do, tensor pointers may be NULL
     if (!Qs || !O_part || !lse || !kv_lens) return FEDRAG_ERR_NULL;
     if (L_kv > 0 && (!Ks || !Vs)) return FEDRAG_ERR_NULL;
     int64_t nq, nk;
@@ -255,7 +255,7 @@ fedrag_status fedrag_partial_attn_quantized(const fedrag_shape* shape, int64_t L
     if (shape->dtype == FEDRAG_F32 || shape->d_head != 128) return FEDRAG_ERR_UNSUPPORTED;
     if (L_q < 0 || L_kv < 0 || L_q > INT32_MAX || L_kv > INT32_MAX) return FEDRAG_ERR_SHAPE;
     if (!attn_uses_decode_kernel(shape->n_q_heads, shape->n_kv_heads, L_q)) return FEDRAG_ERR_UNSUPPORTED;
-    if (L_q == 0) return FEDRAG_OK;  // nothing to do: the tensors have no rows and their pointers may be NULL
+    if (L_q == 0 || shape->batch == 0) return FEDRAG_OK;  // no rows: nothing to do, tensor pointers may be NULL
     if (!Qs || !O_part || !lse) return FEDRAG_ERR_NULL;
     if (L_kv > 0 && (!K_codes || !K_params || !V_codes || !V_params)) return FEDRAG_ERR_NULL;
     int64_t nq, nk;
@@ -289,7 +289,7 @@ fedrag_status fedrag_local_attn(const fedrag_shape* shape, int64_t L_q, int64_t 
     fedrag_status st = check_shape(shape, true);
     if (st != FEDRAG_OK) return st;
     if (L_q < 0 || L_kv < L_q || L_kv > INT32_MAX) return FEDRAG_ERR_SHAPE;  // the queries are among the local tokens
-    if (L_q == 0) return FEDRAG_OK;  // nothing to do: the tensors have no rows and their pointers may be NULL
+    if (L_q == 0 || shape->batch == 0) return FEDRAG_OK;  // no rows: nothing to do, tensor pointers may be NULL
     if (!Q || !O_part || !lse) return FEDRAG_ERR_NULL;
     if (L_kv > 0 && (!K || !V)) return FEDRAG_ERR_NULL;
     int64_t nq, nk;
@@ -322,7 +322,7 @@ fedrag_status fedrag_unpermute_lse(const fedrag_shape* shape, int64_t L_q, const
     fedrag_status st = check_shape(shape, false);
     if (st != FEDRAG_OK) return st;
     if (L_q < 0 || L_q > INT32_MAX) return FEDRAG_ERR_SHAPE;
-    if (L_q == 0) return FEDRAG_OK;  // nothing to do: the tensors have no rows and their pointers may be NULL
+    if (L_q == 0 || shape->batch == 0) return FEDRAG_OK;  // no rows: nothing to do, tensor pointers may be NULL
     if (!lse_scr || !lse_out) return FEDRAG_ERR_NULL;
     const int64_t n_bh = (int64_t)shape->batch * shape->n_q_heads;
     if (L_q != 0 && n_bh > INT64_MAX / 8 / L_q) return FEDRAG_ERR_SHAPE;
@@ -338,7 +338,7 @@ fedrag_status fedrag_lse_merge(const fedrag_shape* shape, int64_t L_q, int32_t n
     fedrag_status st = check_shape(shape, false);
     if (st != FEDRAG_OK) return st;
     if (L_q < 0 || n_shards < 1) return FEDRAG_ERR_SHAPE;
-    if (L_q == 0) return FEDRAG_OK;  // nothing to do: the tensors have no rows and their pointers may be NULL
+    if (L_q == 0 || shape->batch == 0) return FEDRAG_OK;  // no rows: nothing to do, tensor pointers may be NULL
     if (!O_parts || !lses || !O_out || !lse_out) return FEDRAG_ERR_NULL;
     int64_t n;
     if (!tensor_elems(shape->batch, shape->n_q_heads, L_q, shape->d_head, &n)) return FEDRAG_ERR_SHAPE;
@@ -358,7 +358,7 @@ fedrag_status fedrag_unscramble(const fedrag_shape* shape, int64_t L_q, const fl
     fedrag_status st = check_shape(shape, false);
     if (st != FEDRAG_OK) return st;
     if (L_q < 0 || L_q > INT32_MAX) return FEDRAG_ERR_SHAPE;
-    if (L_q == 0) return FEDRAG_OK;  // nothing to do: the tensors have no rows and their pointers may be NULL
+    if (L_q == 0 || shape->batch == 0) return FEDRAG_OK;  // no rows: nothing to do, tensor pointers may be NULL
     if (!O_scr || !phi_v_inv || !O_out) return FEDRAG_ERR_NULL;
     int64_t n;
     if (!tensor_elems(shape->batch, shape->n_q_heads, L_q, shape->d_head, &n)) return FEDRAG_ERR_SHAPE;
@@ -387,7 +387,7 @@ fedrag_status fedrag_unscramble_merge(const fedrag_shape* shape, int64_t L_q, co
     fedrag_status st = check_shape(shape, false);
     if (st != FEDRAG_OK) return st;
     if (L_q < 0 || L_q > INT32_MAX) return FEDRAG_ERR_SHAPE;
-    if (L_q == 0) return FEDRAG_OK;  // nothing to do: the tensors have no rows and their pointers may be NULL
+    if (L_q == 0 || shape->batch == 0) return FEDRAG_OK;  // no rows: nothing to do, tensor pointers may be NULL
     if (!O_scr || !lse_scr || !phi_v_inv || !O_local || !lse_local || !O_out || !lse_out) return FEDRAG_ERR_NULL;
     int64_t n;
     if (!tensor_elems(shape->batch, shape->n_q_heads, L_q, shape->d_head, &n)) return FEDRAG_ERR_SHAPE;
@@ -423,7 +423,7 @@ fedrag_status fedrag_scramble_kv_structured(const fedrag_shape* shape, int64_t L
     fedrag_status st = check_shape(shape, true);
     if (st != FEDRAG_OK) return st;
     if (L_kv < 0 || L_kv > INT32_MAX) return FEDRAG_ERR_SHAPE;
-    if (L_kv == 0) return FEDRAG_OK;  // nothing to do: the tensors have no rows and their pointers may be NULL
+    if (L_kv == 0 || shape->batch == 0) return FEDRAG_OK;  // no rows: nothing to do, tensor pointers may be NULL
     if (!K || !V || !K_out || !V_out) return FEDRAG_ERR_NULL;
     if ((st = check_key(key_k)) != FEDRAG_OK || (st = check_key(key_v)) != FEDRAG_OK) return st;
     if (perm_kv && n_perm != 1 && n_perm != shape->batch) return FEDRAG_ERR_SHAPE;
@@ -460,7 +460,7 @@ fedrag_status fedrag_scramble_q_structured(const fedrag_shape* shape, int64_t L_
     fedrag_status st = check_shape(shape, true);
     if (st != FEDRAG_OK) return st;
     if (L_q < 0 || L_q > INT32_MAX) return FEDRAG_ERR_SHAPE;
-    if (L_q == 0) return FEDRAG_OK;  // nothing to do: the tensors have no rows and their pointers may be NULL
+    if (L_q == 0 || shape->batch == 0) return FEDRAG_OK;  // no rows: nothing to do, tensor pointers may be NULL
     if (!Q || !Q_out) return FEDRAG_ERR_NULL;
     if ((st = check_key(key_q)) != FEDRAG_OK) return st;
     int64_t n;
@@ -492,7 +492,7 @@ fedrag_status fedrag_unscramble_structured(const fedrag_shape* shape, int64_t L_
     fedrag_status st = check_shape(shape, false);
     if (st != FEDRAG_OK) return st;
     if (L_q < 0 || L_q > INT32_MAX) return FEDRAG_ERR_SHAPE;
-    if (L_q == 0) return FEDRAG_OK;  // nothing to do: the tensors have no rows and their pointers may be NULL
+    if (L_q == 0 || shape->batch == 0) return FEDRAG_OK;  // no rows: nothing to do, tensor pointers may be NULL
     if (!O_scr || !O_out) return FEDRAG_ERR_NULL;
     if ((st = check_key(key_v_inv)) != FEDRAG_OK) return st;
     int64_t n;
@@ -528,7 +528,7 @@ static fedrag_status scramble_kv_quantized(const fedrag_shape* shape, int64_t L_
     if (shape->dtype == FEDRAG_F32) return FEDRAG_ERR_UNSUPPORTED;  // the codec epilogue is for 16-bit storage
     if (bits != 8 && bits != 4) return FEDRAG_ERR_UNSUPPORTED;
     if (L_kv < 0 || L_kv > INT32_MAX) return FEDRAG_ERR_SHAPE;
-    if (L_kv == 0) return FEDRAG_OK;  // nothing to do: the tensors have no rows and their pointers may be NULL
+    if (L_kv == 0 || shape->batch == 0) return FEDRAG_OK;  // no rows: nothing to do, tensor pointers may be NULL
     if (!K || !V || !K_codes || !K_params || !V_codes || !V_params) return FEDRAG_ERR_NULL;
     const bool structured = key_k != nullptr || key_v != nullptr;
     if (structured) {

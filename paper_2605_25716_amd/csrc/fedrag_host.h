@@ -63,6 +63,9 @@ struct AttnProblem {
     const int32_t* q_lens;   // NULL, or [B] device array: only the first q_lens[b] query rows of sequence b are computed
                              //   and written (prefill and fp32 kernels; the decode kernel computes all its <= 16 rows)
     bool causal;  // the Lq queries are the last Lq of the Lkv tokens and see nothing after themselves
+    bool single_run;  // one shard only: its keys are one run whatever the planner would choose, so the launch writes
+                      //   (O, lse) directly and touches no workspace (the per-shard launches of a multi-shard call,
+                      //   whose workspace already holds the per-shard partials)
     float* O;     // [B,Hq,Lq,D]
     float* lse;   // [B,Hq,Lq]
     void* workspace;
@@ -108,8 +111,11 @@ hipError_t launch_decode_attn(const AttnProblem& p, hipStream_t stream);   // 16
 hipError_t launch_prefill_attn(const AttnProblem& p, hipStream_t stream);  // 16-bit storage, any L_q
 
 // Aggregation of S partials: O_parts [S, rows, D], lses [S, rows] -> O [rows, D], lse [rows].
+// q_lens (device, [B]) with Lq and rows_per_seq = Hq * Lq: row r is query r % Lq of sequence r / rows_per_seq, and rows
+// at or past q_lens[sequence] are skipped (neither read nor written).
 hipError_t launch_lse_merge(const float* O_parts, const float* lses, int S, int64_t rows, int D, float* O, float* lse,
-                            hipStream_t stream);
+                            hipStream_t stream, const int32_t* q_lens = nullptr, int64_t Lq = 1,
+                            int64_t rows_per_seq = 1);
 // O = 0, lse = -inf for `rows` rows (a shard with no keys).
 hipError_t launch_fill_empty(float* O, float* lse, int64_t rows, int D, hipStream_t stream);
 // out[bh, perm[i]] = in[bh, i] for n_bh rows of L values each (perm NULL = copy).

@@ -10,12 +10,16 @@ namespace fedrag {
 template <int D>
 __global__ __launch_bounds__(256) void lse_merge_kernel(const float* __restrict__ O_parts,
                                                         const float* __restrict__ lses, int S, int64_t rows,
-                                                        float* __restrict__ O, float* __restrict__ lse) {
+                                                        float* __restrict__ O, float* __restrict__ lse,
+                                                        const int32_t* __restrict__ q_lens, int64_t Lq,
+                                                        int64_t rows_per_seq) {
     constexpr int TPR = D / 4;  // threads per row
     const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     const int64_t r = gid / TPR;
     const int c4 = (int)(gid % TPR) * 4;
     if (r >= rows) return;
+    // padded batch with per-sequence query counts: padding rows hold no partials and are not written
+    if (q_lens && (r % Lq) >= q_lens[r / rows_per_seq]) return;
     float M = -INFINITY;
     for (int i = 0; i < S; ++i) M = fmaxf(M, lses[(int64_t)i * rows + r]);
     f32x4_t acc = zero_vec<f32x4_t>();
@@ -52,14 +56,17 @@ __global__ __launch_bounds__(256) void fill_empty_kernel(float* __restrict__ O, 
 }
 
 hipError_t launch_lse_merge(const float* O_parts, const float* lses, int S, int64_t rows, int D, float* O, float* lse,
-                            hipStream_t stream) {
+                            hipStream_t stream, const int32_t* q_lens, int64_t Lq, int64_t rows_per_seq) {
     if (rows == 0) return hipSuccess;
+    if (q_lens && (Lq < 1 || rows_per_seq < 1)) return hipErrorInvalidValue;
     const int64_t threads = rows * (D / 4);
     const dim3 grid((unsigned)((threads + 255) / 256));
     if (D == 128)
-        hipLaunchKernelGGL(lse_merge_kernel<128>, grid, dim3(256), 0, stream, O_parts, lses, S, rows, O, lse);
+        hipLaunchKernelGGL(lse_merge_kernel<128>, grid, dim3(256), 0, stream, O_parts, lses, S, rows, O, lse,
+                           q_lens, Lq, rows_per_seq);
     else
-        hipLaunchKernelGGL(lse_merge_kernel<64>, grid, dim3(256), 0, stream, O_parts, lses, S, rows, O, lse);
+        hipLaunchKernelGGL(lse_merge_kernel<64>, grid, dim3(256), 0, stream, O_parts, lses, S, rows, O, lse,
+                           q_lens, Lq, rows_per_seq);
     return hipGetLastError();
 }
 

@@ -10,9 +10,8 @@ scramble, 16-bit storage: the kernel accumulates the d exact products of a row i
                  bounded by d * 2^-24 * sum_k |x_k Phi_kj| <= 1e-5 * sum_k |x_k Phi_kj| for d <= 128:
                      |gpu - round(oracle)| <= ulp_storage(oracle) + 2e-5 * sum_k |x_k| |Phi_kj|
                  and at least 97 % of the elements must match bit for bit.
-16-bit path on plaintext V (the Inquirer's local attention; outlier channels not spread by Phi, |v| up to ~80):
-                 the probabilities enter the second product in the storage type (relative rounding 2^-9 bf16), so
-                 the output bound scales with the values: 2e-2 * max(1, max|V| / 8).  lse bound unchanged.
+                 One flat output bound for every 16-bit attention call, the Inquirer's local attention on
+                 plaintext V (outlier channels not spread by Phi, |v| up to ~80) included.
 Index work     : bit-exact.
 """
 import numpy as np
@@ -48,16 +47,20 @@ def max_abs(got, ref):
     return float(np.abs(got[fin] - ref[fin]).max()) if fin.any() else 0.0
 
 
-def check_attn(got_O, got_lse, ref_O, ref_lse, dtype, what="", v_absmax=None):
-    """v_absmax: max |V| when V is plaintext with concentrated outlier channels (scales the 16-bit output bound)."""
+def check_attn(got_O, got_lse, ref_O, ref_lse, dtype, what="", report=False):
+    """Returns the observed (output, lse) errors; report=True also prints them (pytest -s / a failing test shows it)."""
     if dtype == torch.float32:
         eo, el = rel_normwise(got_O, ref_O), rel_normwise(got_lse, ref_lse)
+        if report:
+            print(f"{what}: observed O rel err {eo:.3e}, lse rel err {el:.3e} (bound {TOL_F32_REL:.0e})")
         assert eo <= TOL_F32_REL, f"{what}: O rel err {eo:.3e}"
         assert el <= TOL_F32_REL, f"{what}: lse rel err {el:.3e}"
     else:
         eo, el = max_abs(got_O, ref_O), max_abs(got_lse, ref_lse)
-        tol_o = TOL_16_OUT_ABS * (1.0 if v_absmax is None else max(1.0, float(v_absmax) / 8.0))
-        assert eo <= tol_o, f"{what}: O abs err {eo:.3e} > {tol_o:.3e}"
+        if report:
+            print(f"{what}: observed O abs err {eo:.3e} (bound {TOL_16_OUT_ABS:.0e}), lse abs err {el:.3e} "
+                  f"(bound {TOL_16_LSE_ABS:.0e})")
+        assert eo <= TOL_16_OUT_ABS, f"{what}: O abs err {eo:.3e} > {TOL_16_OUT_ABS:.0e}"
         assert el <= TOL_16_LSE_ABS, f"{what}: lse abs err {el:.3e}"
     return eo, el
 

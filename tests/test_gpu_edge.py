@@ -60,3 +60,28 @@ def test_single_row_everything():
     assert float((O - Vs.float()).abs().max()) == 0.0
     assert float((out - V.float()).abs().max()) <= 2e-2
     assert np.isfinite(float(lse))
+
+
+def test_zero_sequences():
+    """batch = 0 is a legal shape: every call returns at once and writes nothing."""
+    dtype = torch.bfloat16
+    Hq, Hkv, d = 4, 2, 128
+    keys = W.make_keys(Hkv, d, 3, 8, 1, seed=5, dtype=dtype)
+    z = lambda H, L: torch.zeros((0, H, L, d), dtype=dtype, device=DEV)
+    phi = lambda n: getattr(keys, n).to(DEV)
+    assert fb.fedrag_scramble_q(z(Hq, 3), phi("phi_q"), None).shape == (0, Hq, 3, d)
+    Ks, Vs = fb.fedrag_scramble_kv(z(Hkv, 8), z(Hkv, 8), phi("phi_k"), phi("phi_v"), None, n_q_heads=Hq)
+    assert Ks.shape == (0, Hkv, 8, d)
+    for Lq in (1, 300):  # decode kernel and prefill kernel
+        O, lse = fb.fedrag_partial_attn(z(Hq, Lq), z(Hkv, 8), z(Hkv, 8))
+        assert O.shape == (0, Hq, Lq, d) and lse.shape == (0, Hq, Lq)
+        O, lse = fb.fedrag_partial_attn_shards(z(Hq, Lq), [z(Hkv, 8), z(Hkv, 5)], [z(Hkv, 8), z(Hkv, 5)])
+        assert O.shape == (0, Hq, Lq, d)
+        O, lse = fb.fedrag_local_attn(z(Hq, Lq), z(Hkv, 300), z(Hkv, 300))
+        assert O.shape == (0, Hq, Lq, d)
+    Om, lm = fb.fedrag_lse_merge(torch.zeros((2, 0, Hq, 3, d), device=DEV), torch.zeros((2, 0, Hq, 3), device=DEV),
+                                 n_kv_heads=Hkv)
+    assert Om.shape == (0, Hq, 3, d)
+    out = fb.fedrag_unscramble(torch.zeros((0, Hq, 3, d), device=DEV), phi("phi_v_inv"), None)
+    assert out.shape == (0, Hq, 3, d)
+    torch.cuda.synchronize()

@@ -25,6 +25,11 @@ CASES = [
     # enough query tiles to cover the chip: one run per shard
     ("pre_bf16_walk", 4, 8, 2, 128, 1100, [200, 0, 333], "bf16"),
     ("f32", 2, 4, 2, 128, 3, [197, 0, 50], "f32"),
+    # prefill shapes where all shards together plan one run per shard (so the call launches shard by shard) while a
+    # shard alone would be cut into runs: the per-shard launches must not cut, the workspace holds the shards' partials
+    ("pre_bf16_two_shards_one_run_each", 1, 32, 8, 64, 1024, [1024, 1024], "bf16"),
+    ("pre_bf16_16_shards_one_run_each", 2, 32, 8, 64, 64, [512] * 16, "bf16"),
+    ("pre_f16_4_shards_one_run_each", 1, 32, 8, 128, 512, [1024] * 4, "f16"),
 ]
 
 
@@ -50,6 +55,18 @@ def test_shards_equal_per_shard_then_merge_and_concatenation(oracle, case):
     # oracle, eq. (1) over all keys at once
     Oc, lc = oracle.partial_attn(Q, torch.cat(Ks, dim=2), torch.cat(Vs, dim=2))
     PT.check_attn(O, lse, Oc, lc, dtype, name + " vs concatenated keys")
+
+
+def test_planner_geometries_launch_shard_by_shard():
+    """The three cases above exist for one geometry: more than one run for a shard on its own, one run per shard for
+    all of them together.  The workspace sizes say which plan the library made."""
+    for (B, Hq, Hkv, d, Lq, Ls) in [(1, 32, 8, 64, 1024, [1024, 1024]), (2, 32, 8, 64, 64, [512] * 16),
+                                     (1, 32, 8, 128, 512, [1024] * 4)]:
+        per_part = B * Hq * Lq * (d + 1) * 4
+        alone = fb.fedrag_partial_attn_workspace_bytes(B, Hq, Hkv, d, torch.bfloat16, Lq, Ls[0])
+        together = fb.fedrag_partial_attn_shards_workspace_bytes(B, Hq, Hkv, d, torch.bfloat16, Lq, Ls)
+        assert alone >= 2 * per_part, "a shard alone is no longer cut into runs: pick another geometry"
+        assert together == len(Ls) * per_part, "all shards together no longer plan one run per shard"
 
 
 def test_one_shard_is_partial_attn_bit_for_bit():

@@ -20,8 +20,9 @@ CASES = [
 ]
 
 
+@pytest.mark.parametrize("poison", ["huge", "nan", "inf"])
 @pytest.mark.parametrize("case", CASES, ids=[c[0] for c in CASES])
-def test_partial_attn_varlen(oracle, case):
+def test_partial_attn_varlen(oracle, case, poison):
     name, B, Hq, Hkv, d, Lq, L, dt, lens = case
     dtype = W.torch_dtype(dt)
     seed = 500 + len(name)
@@ -33,14 +34,19 @@ def test_partial_attn_varlen(oracle, case):
     Qs, Ks, Vs = rnd(oracle.scramble(Q, keys.phi_q, None)), rnd(oracle.scramble(K, keys.phi_k, None)), \
         rnd(oracle.scramble(V, keys.phi_v, None))
     lens_t = torch.tensor(lens, dtype=torch.int32)
-    # poison the padding: it must not reach the result
+    # poison the padding: it must not reach the result, not even through a product with a zero probability
+    pk, pv = {"huge": (3.0e4 if dt != "bf16" else 1.0e30, -3.0e4 if dt != "bf16" else -1.0e30),
+              "nan": (float("nan"), float("nan")), "inf": (float("inf"), -float("inf"))}[poison]
     for b, n in enumerate(lens):
-        Ks[b, :, n:] = 3.0e4 if dt != "bf16" else 1.0e30
-        Vs[b, :, n:] = -3.0e4 if dt != "bf16" else -1.0e30
+        Ks[b, :, n:] = pk
+        Vs[b, :, n:] = pv
     O, lse = fb.fedrag_partial_attn_varlen(Qs.to(DEV), Ks.to(DEV), Vs.to(DEV), lens_t.to(DEV))
     torch.cuda.synchronize()
+    for b, n in enumerate(lens):  # the oracle never touches the padding either; give it finite values all the same
+        Ks[b, :, n:] = 0
+        Vs[b, :, n:] = 0
     Or, lr = oracle.partial_attn_varlen(Qs, Ks, Vs, lens_t)
-    PT.check_attn(O, lse, Or, lr, dtype, name)
+    PT.check_attn(O, lse, Or, lr, dtype, f"{name}/{poison}")
 
 
 @pytest.mark.parametrize("dt,d", [("bf16", 64), ("f32", 64)])
@@ -60,6 +66,28 @@ def test_query_lengths_skip_padding_rows(oracle, dt, d):
     torch.cuda.synchronize()
     Or, lr = oracle.partial_attn_varlen(Q, K, V, lens_t)
     for b, n in enumerate(lens):
+        if n:
+            PT.check_attn(O[b:b + 1, :, :n], lse[b:b + 1, :, :n], Or[b:b + 1, :, :n], lr[b:b + 1, :, :n], dtype, f"seq {b}")
+        assert bool((O[b, :, n:] == 7.0).all()) and bool((lse[b, :, n:] == 7.0).all()), "padding rows were written"
+
+
+@pytest.mark.parametrize("L", [100, 3000])
+def test_query_lengths_decode_shape(oracle, L):
+    """Per-sequence query counts on a decode-shaped call (G * L_q <= 16: the streaming kernel, with L = 3000 also its
+    key runs and their aggregation): rows past a sequence's count keep what they held."""
+    dtype = torch.bfloat16
+    B, Hq, Hkv, d, Lq = 4, 8, 2, 128, 4
+    q_lens, kv_lens = [4, 2, 0, 3], [L, L // 3, 17, 0]
+    seed = 4242
+    mk = lambda H, n, tid: W.activations(B, H, n, d, seed=seed, tensor_id=tid, outliers=False, dtype=dtype)
+    Q, K, V = mk(Hq, Lq, W.TID_Q), mk(Hkv, L, W.TID_K), mk(Hkv, L, W.TID_V)
+    ql, kl = torch.tensor(q_lens, dtype=torch.int32), torch.tensor(kv_lens, dtype=torch.int32)
+    O = torch.full((B, Hq, Lq, d), 7.0, dtype=torch.float32, device=DEV)
+    lse = torch.full((B, Hq, Lq), 7.0, dtype=torch.float32, device=DEV)
+    fb.fedrag_partial_attn_varlen(Q.to(DEV), K.to(DEV), V.to(DEV), kl.to(DEV), O_part=O, lse=lse, q_lens=ql.to(DEV))
+    torch.cuda.synchronize()
+    Or, lr = oracle.partial_attn_varlen(Q, K, V, kl)
+    for b, n in enumerate(q_lens):
         if n:
             PT.check_attn(O[b:b + 1, :, :n], lse[b:b + 1, :, :n], Or[b:b + 1, :, :n], lr[b:b + 1, :, :n], dtype, f"seq {b}")
         assert bool((O[b, :, n:] == 7.0).all()) and bool((lse[b, :, n:] == 7.0).all()), "padding rows were written"
