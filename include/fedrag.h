@@ -111,6 +111,25 @@ fedrag_status fedrag_partial_attn(const fedrag_shape* shape, int64_t L_q, int64_
 size_t fedrag_partial_attn_workspace_bytes(const fedrag_shape* shape, int64_t L_q, int64_t L_kv);
 
 /*
+ * fedrag_partial_attn for callers that cannot allocate device memory and so have no workspace to pass: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid allocation.  Same arguments (less the workspace), same
+ * kernels, same results; the key-run partials land in a static device array of FEDRAG_STATIC_SCRATCH_BYTES bytes that
+ * is part of the library's code object (each GPU the library runs on holds its copy until the process ends).  The
+ * call allocates and frees nothing.  Sizes whose fedrag_partial_attn_workspace_bytes() exceeds
+ * FEDRAG_STATIC_SCRATCH_BYTES are refused with FEDRAG_ERR_WORKSPACE and nothing is launched (every decode shape,
+ * (n_q_heads / n_kv_heads) * L_q <= 16, needs at most about 4.3 MB).
+ * All calls on one GPU share that GPU's array: calls that may overlap in time on one GPU (different streams, or
+ * graphs replayed concurrently) race on it and must be serialised by the caller; calls on one stream are safe.
+ * Nothing has to be cleared between calls: every partial a launch reads, it has written itself.
+ * The first call on a device looks the array's device address up (no allocation, but not a stream operation):
+ * make it once outside any graph capture.  A failed lookup returns FEDRAG_ERR_DEVICE.
+ */
+#define FEDRAG_STATIC_SCRATCH_BYTES (16u << 20)
+fedrag_status fedrag_partial_attn_static(const fedrag_shape* shape, int64_t L_q, int64_t L_kv,
+                                         const void* Qs, const void* Ks, const void* Vs, float softmax_scale,
+                                         float* O_part, float* lse, void* stream);
+
+/*
  * Section 4.1 as a whole on a Compute Node that holds the shards of several Context Owners for the same queries:
  * the per-shard computation of fedrag_partial_attn on each of the n_shards shards and the aggregation of
  * fedrag_lse_merge over them, in one call (one attention launch over all shards' keys plus one aggregation launch,

@@ -18,7 +18,9 @@ OK, ERR_NULL, ERR_SHAPE, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_ALIAS, ERR_DEVICE =
 F32, BF16, F16 = 0, 1, 2
 _DTYPES = {torch.float32: F32, torch.bfloat16: BF16, torch.float16: F16}
 
-EXPORTS = ("fedrag_scramble_kv", "fedrag_scramble_q", "fedrag_partial_attn",
+STATIC_SCRATCH_BYTES = 16 << 20  # FEDRAG_STATIC_SCRATCH_BYTES
+
+EXPORTS = ("fedrag_scramble_kv", "fedrag_scramble_q", "fedrag_partial_attn", "fedrag_partial_attn_static",
            "fedrag_partial_attn_workspace_bytes", "fedrag_partial_attn_shards",
            "fedrag_partial_attn_shards_workspace_bytes", "fedrag_lse_merge", "fedrag_unscramble", "fedrag_unscramble_merge",
            "fedrag_scramble_kv_structured", "fedrag_scramble_q_structured", "fedrag_unscramble_structured",
@@ -68,6 +70,7 @@ def load() -> ctypes.CDLL:
         lib.fedrag_partial_attn.argtypes = [sp, i64, i64, vp, vp, vp, ctypes.c_float, f32p, f32p, vp,
                                             ctypes.c_size_t, vp]
         lib.fedrag_local_attn.argtypes = lib.fedrag_partial_attn.argtypes
+        lib.fedrag_partial_attn_static.argtypes = [sp, i64, i64, vp, vp, vp, ctypes.c_float, f32p, f32p, vp]
         lib.fedrag_partial_attn_shards.argtypes = [sp, i64, ctypes.c_int32, ctypes.POINTER(ctypes.c_int64),
                                                    ctypes.POINTER(ctypes.c_void_p), ctypes.POINTER(ctypes.c_void_p),
                                                    vp, ctypes.c_float, f32p, f32p, vp, ctypes.c_size_t, vp]
@@ -96,7 +99,7 @@ def load() -> ctypes.CDLL:
         lib.fedrag_status_string.argtypes = [ctypes.c_int]
         lib.fedrag_status_string.restype = ctypes.c_char_p
         lib.fedrag_version.restype = ctypes.c_int
-        for name in ("fedrag_scramble_kv", "fedrag_scramble_q", "fedrag_partial_attn",
+        for name in ("fedrag_scramble_kv", "fedrag_scramble_q", "fedrag_partial_attn", "fedrag_partial_attn_static",
                      "fedrag_partial_attn_shards", "fedrag_unscramble_merge", "fedrag_lse_merge",
                      "fedrag_unscramble", "fedrag_invert_perm", "fedrag_scramble_kv_structured",
                      "fedrag_scramble_q_structured", "fedrag_unscramble_structured", "fedrag_local_attn",
@@ -194,6 +197,21 @@ def fedrag_partial_attn(Qs, Ks, Vs, softmax_scale: Optional[float] = None, O_par
                                     _ptr(Vs) if L > 0 else None, ctypes.c_float(softmax_scale), _ptr(O_part),
                                     _ptr(lse), _ptr(workspace), ws_bytes, _stream())
     _check(st, "fedrag_partial_attn")
+    return O_part, lse
+
+
+def fedrag_partial_attn_static(Qs, Ks, Vs, O_part, lse, softmax_scale: Optional[float] = None):
+    """fedrag_partial_attn without a workspace argument (the library's static scratch array); the caller passes the
+    outputs, so that the call allocates nothing."""
+    B, Hq, Lq, d = Qs.shape
+    Hkv, L = Ks.shape[1], Ks.shape[2]
+    shape = make_shape(B, Hq, Hkv, d, Qs.dtype)
+    if softmax_scale is None:
+        softmax_scale = float(d) ** -0.5
+    st = load().fedrag_partial_attn_static(ctypes.byref(shape), Lq, L, _ptr(Qs), _ptr(Ks) if L > 0 else None,
+                                           _ptr(Vs) if L > 0 else None, ctypes.c_float(softmax_scale), _ptr(O_part),
+                                           _ptr(lse), _stream())
+    _check(st, "fedrag_partial_attn_static")
     return O_part, lse
 
 

@@ -228,6 +228,32 @@ static hipError_t launch_attn_f32(const AttnProblem& p, hipStream_t stream) {
     return hipGetLastError();
 }
 
+// Scratch for callers that cannot allocate: the key-run partials of a launch land in this file-scope device array
+// instead of a caller's workspace.  Every GPU the library runs on holds its own copy (at its own address) until the
+// process ends.  The name below is only the host's handle for the symbol: the device address is looked up once per
+// device, with that device current, and only that pointer is ever handed to a kernel.
+namespace {
+__attribute__((used)) static __device__ __align__(256) unsigned char scratch[FEDRAG_STATIC_SCRATCH_BYTES];
+}
+
+hipError_t attn_static_scratch(void** ptr_out) {
+    constexpr int kMaxDev = 64;
+    static std::atomic<void*> ptrs[kMaxDev];
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDev) return hipErrorInvalidDevice;
+    void* p = ptrs[dev].load(std::memory_order_acquire);
+    if (!p) {  // first call on this device (concurrent first calls look the same address up twice)
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        ptrs[dev].store(p, std::memory_order_release);
+    }
+    *ptr_out = p;
+    return hipSuccess;
+}
+
 hipError_t launch_partial_attn(const AttnProblem& p_in, hipStream_t stream) {
     AttnProblem p = p_in;
     if (p.Lq == 1) p.causal = false;  // a single query at the last position sees every key

@@ -160,6 +160,42 @@ fedrag_status fedrag_partial_attn(const fedrag_shape* shape, int64_t L_q, int64_
     return dev(launch_partial_attn(p, (hipStream_t)stream));
 }
 
+fedrag_status fedrag_partial_attn_static(const fedrag_shape* shape, int64_t L_q, int64_t L_kv, const void* Qs,
+                                         const void* Ks, const void* Vs, float softmax_scale, float* O_part,
+                                         float* lse, void* stream) {
+    fedrag_status st = check_shape(shape, true);
+    if (st != FEDRAG_OK) return st;
+    if (L_q < 0 || L_kv < 0 || L_q > INT32_MAX || L_kv > INT32_MAX) return FEDRAG_ERR_SHAPE;
+    if (L_q == 0 || shape->batch == 0) return FEDRAG_OK;  // no rows: nothing to do, tensor pointers may be NULL
+    if (!Qs || !O_part || !lse) return FEDRAG_ERR_NULL;
+    if (L_kv > 0 && (!Ks || !Vs)) return FEDRAG_ERR_NULL;
+    int64_t nq, nk;
+    if (!tensor_elems(shape->batch, shape->n_q_heads, L_q, shape->d_head, &nq) ||
+        !tensor_elems(shape->batch, shape->n_kv_heads, L_kv, shape->d_head, &nk))
+        return FEDRAG_ERR_SHAPE;
+    if (!(softmax_scale > 0.0f) || softmax_scale - softmax_scale != 0.0f) return FEDRAG_ERR_SHAPE;  // finite, > 0
+    if (!aligned16(Qs) || !aligned16(Ks) || !aligned16(Vs) || !aligned16(O_part) ||
+        (reinterpret_cast<uintptr_t>(lse) & 3u))
+        return FEDRAG_ERR_ALIAS;
+    const size_t need = attn_workspace_bytes(shape->batch, shape->n_q_heads, shape->n_kv_heads, shape->d_head,
+                                             shape->dtype, L_q, L_kv);
+    if (need > (size_t)FEDRAG_STATIC_SCRATCH_BYTES) return FEDRAG_ERR_WORKSPACE;  // beyond the static array
+    void* scratch_ptr = nullptr;
+    if (need > 0 && attn_static_scratch(&scratch_ptr) != hipSuccess) {
+        (void)hipGetLastError();
+        return FEDRAG_ERR_DEVICE;
+    }
+    AttnProblem p{};
+    p.B = shape->batch; p.Hq = shape->n_q_heads; p.Hkv = shape->n_kv_heads; p.D = shape->d_head;
+    p.dtype = shape->dtype;
+    p.Lq = L_q; p.Lkv = L_kv;
+    p.Q = Qs; p.K = Ks; p.V = Vs;
+    p.scale = softmax_scale;
+    p.O = O_part; p.lse = lse;
+    p.workspace = scratch_ptr; p.workspace_bytes = need > 0 ? (size_t)FEDRAG_STATIC_SCRATCH_BYTES : 0;
+    return dev(launch_partial_attn(p, (hipStream_t)stream));
+}
+
 size_t fedrag_partial_attn_shards_workspace_bytes(const fedrag_shape* shape, int64_t L_q, int32_t n_shards,
                                                   const int64_t* L_kv) {
     if (check_shape(shape, true) != FEDRAG_OK || L_q < 0 || n_shards < 1 || n_shards > kMaxShards || !L_kv) return 0;

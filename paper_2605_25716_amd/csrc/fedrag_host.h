@@ -95,6 +95,8 @@ inline size_t attn_workspace_bytes(int B, int Hq, int Hkv, int D, int dtype, int
 // The plan of problem p with its pointers filled in.
 KeyRuns attn_runs_of(const AttnProblem& p);
 hipError_t launch_partial_attn(const AttnProblem& p, hipStream_t stream);
+// Device address, on the current device, of the library's static scratch array of FEDRAG_STATIC_SCRATCH_BYTES bytes.
+hipError_t attn_static_scratch(void** ptr_out);
 
 // decode kernel geometry (shared by the split planner and the kernel)
 constexpr int kDecWaves = 4;
