@@ -328,6 +328,19 @@ fedrag_status fedrag_partial_attn_quantized(const fedrag_shape* shape, int64_t L
 /* inv_out[perm[j]] = j for j in [0, L): the gather array that undoes `perm`.  Device pointers. */
 fedrag_status fedrag_invert_perm(const int32_t* perm, int64_t L, int32_t* inv_out, void* stream);
 
+/*
+ * Debug aid for the key holders (the token-permutation paragraph of Section 4.2 needs P_Q, P_KV to be permutations;
+ * the calls above take that on trust and gather / scatter through the indices unchecked): checks that each of the
+ * n_perm rows of perm ([n_perm, L] int32, DEVICE) holds every index 0..L-1 exactly once.
+ * marks    : DEVICE scratch of n_perm * L int32 (contents destroyed), 4-byte aligned.
+ * flag_out : DEVICE int32; receives 0 when every row is a permutation, else bit 0 = some index lies outside
+ *            [0, L), bit 1 = some index occurs more than once.
+ * Enqueues two small kernels and returns; read flag_out after synchronising with the stream.  n_perm >= 1, L >= 0
+ * (L == 0: flag_out = 0), n_perm * L < 2^40, else FEDRAG_ERR_SHAPE.
+ */
+fedrag_status fedrag_validate_perm(const int32_t* perm, int32_t n_perm, int64_t L, int32_t* marks, int32_t* flag_out,
+                                   void* stream);
+
 /* Static, human-readable name of a status code (host pointer, never NULL). */
 const char* fedrag_status_string(fedrag_status status);
 

@@ -26,7 +26,8 @@ EXPORTS = ("fedrag_scramble_kv", "fedrag_scramble_q", "fedrag_partial_attn", "fe
            "fedrag_scramble_kv_structured", "fedrag_scramble_q_structured", "fedrag_unscramble_structured",
            "fedrag_local_attn", "fedrag_unpermute_lse", "fedrag_partial_attn_varlen", "fedrag_quantize_rows",
            "fedrag_dequantize_rows", "fedrag_scramble_kv_quantized", "fedrag_scramble_kv_structured_quantized",
-           "fedrag_partial_attn_quantized", "fedrag_invert_perm", "fedrag_status_string", "fedrag_version")
+           "fedrag_partial_attn_quantized", "fedrag_invert_perm", "fedrag_validate_perm", "fedrag_status_string",
+           "fedrag_version")
 
 
 class Shape(ctypes.Structure):
@@ -96,12 +97,13 @@ def load() -> ctypes.CDLL:
         lib.fedrag_partial_attn_quantized.argtypes = [sp, i64, i64, vp, vp, vp, vp, vp, i32, ctypes.c_float, f32p, f32p,
                                                       vp, ctypes.c_size_t, vp]
         lib.fedrag_invert_perm.argtypes = [vp, i64, vp, vp]
+        lib.fedrag_validate_perm.argtypes = [vp, i32, i64, vp, vp, vp]
         lib.fedrag_status_string.argtypes = [ctypes.c_int]
         lib.fedrag_status_string.restype = ctypes.c_char_p
         lib.fedrag_version.restype = ctypes.c_int
         for name in ("fedrag_scramble_kv", "fedrag_scramble_q", "fedrag_partial_attn", "fedrag_partial_attn_static",
                      "fedrag_partial_attn_shards", "fedrag_unscramble_merge", "fedrag_lse_merge",
-                     "fedrag_unscramble", "fedrag_invert_perm", "fedrag_scramble_kv_structured",
+                     "fedrag_unscramble", "fedrag_invert_perm", "fedrag_validate_perm", "fedrag_scramble_kv_structured",
                      "fedrag_scramble_q_structured", "fedrag_unscramble_structured", "fedrag_local_attn",
                      "fedrag_unpermute_lse", "fedrag_partial_attn_varlen", "fedrag_quantize_rows",
                      "fedrag_dequantize_rows", "fedrag_scramble_kv_quantized",
@@ -471,3 +473,15 @@ def fedrag_invert_perm(perm, inv_out=None):
     st = load().fedrag_invert_perm(_ptr(perm), perm.numel(), _ptr(inv_out), _stream())
     _check(st, "fedrag_invert_perm")
     return inv_out
+
+
+def fedrag_validate_perm(perm, flag_out=None, marks=None):
+    """Debug aid: device int32 flag, 0 when every row of perm ([L] or [n_perm, L] int32) is a permutation of 0..L-1,
+    else bit 0 = an index out of range, bit 1 = an index repeated.  Read it after synchronising."""
+    n_perm = 1 if perm.dim() == 1 else perm.shape[0]
+    L = perm.shape[-1]
+    flag_out = torch.empty(1, dtype=torch.int32, device=perm.device) if flag_out is None else flag_out
+    marks = torch.empty(max(1, n_perm * L), dtype=torch.int32, device=perm.device) if marks is None else marks
+    st = load().fedrag_validate_perm(_ptr(perm), n_perm, L, _ptr(marks), _ptr(flag_out), _stream())
+    _check(st, "fedrag_validate_perm")
+    return flag_out

@@ -77,6 +77,39 @@ def build_library(force: bool = True, verbose: bool = False, extra_flags=(), job
     return LIB_PATH
 
 
+SAN_DIR = os.path.join(OBJ_DIR, "san")
+SAN_FLAGS = ["-O1", "-g", "-fno-omit-frame-pointer",
+             # host code only: each -fsanitize= goes directly behind an -Xarch_host (the device side has no sanitizer)
+             "-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
+             "-Xarch_host", "-fno-sanitize-recover=undefined"]
+
+
+def build_host_check(c_driver: str, force: bool = False, verbose: bool = False, jobs: int = 8) -> str:
+    """The library's sources with their HOST code under AddressSanitizer + UndefinedBehaviorSanitizer, linked with a
+    C driver into one executable (returned path).  Used by the CPU tests to walk the argument checks, the key-run
+    planner and the workspace queries; the driver makes no call that reaches a kernel launch."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    clang = os.path.join(os.path.dirname(os.path.realpath(hipcc)), "..", "lib", "llvm", "bin", "clang")
+    if not os.path.exists(clang):
+        clang = "/opt/rocm/lib/llvm/bin/clang"
+    os.makedirs(SAN_DIR, exist_ok=True)
+    exe = os.path.join(SAN_DIR, os.path.splitext(os.path.basename(c_driver))[0])
+    deps = sources() + _headers() + [c_driver, os.path.abspath(__file__)]
+    if not force and os.path.exists(exe) and all(os.path.getmtime(d) <= os.path.getmtime(exe) for d in deps):
+        return exe
+    obj = lambda s_: os.path.join(SAN_DIR, os.path.splitext(os.path.basename(s_))[0] + ".o")
+    flags = [f for f in HIPCC_FLAGS if f != "-O3"] + SAN_FLAGS
+    cmds = [[hipcc] + flags + ["-c", s_, "-o", obj(s_)] for s_ in sources()]
+    include = os.path.join(_HERE, "..", "include")
+    cmds.append([clang, "-std=c99", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined",
+                 "-I", include, "-c", c_driver, "-o", obj(c_driver)])
+    with ThreadPoolExecutor(max_workers=max(1, min(jobs, len(cmds)))) as pool:
+        list(pool.map(lambda c: _run(c, verbose), cmds))
+    _run([hipcc, "--offload-arch=gfx950", "-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
+          "-o", exe] + [obj(s_) for s_ in sources()] + [obj(c_driver)], verbose)
+    return exe
+
+
 if __name__ == "__main__":
     import sys
     print(build_library(force="--incremental" not in sys.argv, verbose=True))

@@ -222,6 +222,7 @@ size_t attn_workspace_bytes(int B, int Hq, int Hkv, int D, int dtype, int64_t Lq
 template <int D>
 static hipError_t launch_attn_f32(const AttnProblem& p, hipStream_t stream) {
     const int64_t rows = (int64_t)p.B * p.Hq * p.Lq;
+    if (!grid_fits((rows + 3) / 4)) return hipErrorInvalidValue;
     hipLaunchKernelGGL(attn_f32_kernel<D>, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, stream, (const float*)p.Q,
                        (const float*)p.K, (const float*)p.V, p.Hq, p.Hkv, p.Lq, p.Lkv, p.causal ? 1 : 0, rows, p.scale,
                        p.O, p.lse, p.kv_lens, p.q_lens);

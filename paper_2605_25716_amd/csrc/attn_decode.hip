@@ -462,6 +462,7 @@ static hipError_t launch_decode_t(const AttnProblem& p, hipStream_t stream) {
         Odst = (float*)p.workspace;
         Ldst = Odst + (size_t)splits * rows * D;
     }
+    if (!grid_fits(units * splits)) return hipErrorInvalidValue;
     hipLaunchKernelGGL((decode_attn_kernel<T, D, QB>), dim3((unsigned)(units * splits)), dim3(kDecThreads), 0, stream,
                        (const elem*)p.Q, runs, p.K_params, p.V_params, R, scale_log2, Odst, Ldst, rows, p.kv_lens,
                        p.q_lens, (int)p.Lq, p.Hkv);

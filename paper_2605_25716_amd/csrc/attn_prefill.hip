@@ -470,8 +470,9 @@ static hipError_t launch_prefill_t(const AttnProblem& p, hipStream_t stream) {
         Odst = (float*)p.workspace;
         Ldst = Odst + (size_t)splits * rows * D;
     }
-    const int per_unit = (Hq_k / p.Hkv) * q_tiles * splits;
+    const int64_t per_unit = (int64_t)(Hq_k / p.Hkv) * q_tiles * splits;
     const int64_t grid = (int64_t)8 * ((n_units + 7) / 8) * per_unit;
+    if (!grid_fits(grid)) return hipErrorInvalidValue;
     hipLaunchKernelGGL((prefill_attn_kernel<T, D, CAUSAL>), dim3((unsigned)grid), dim3(kPreThreads), 0, stream,
                        (const elem*)p.Q, runs, Hq_k, p.Hkv, Lq_k, p.kv_lens, p.q_lens, q_tiles, n_units, scale_log2,
                        Odst, Ldst);

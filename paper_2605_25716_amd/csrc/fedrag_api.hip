@@ -669,6 +669,19 @@ fedrag_status fedrag_invert_perm(const int32_t* perm, int64_t L, int32_t* inv_ou
     return dev(launch_invert_perm(perm, L, inv_out, (hipStream_t)stream));
 }
 
+fedrag_status fedrag_validate_perm(const int32_t* perm, int32_t n_perm, int64_t L, int32_t* marks, int32_t* flag_out,
+                                   void* stream) {
+    if (n_perm < 1 || L < 0 || L > INT32_MAX || (int64_t)n_perm * L >= ((int64_t)1 << 40)) return FEDRAG_ERR_SHAPE;
+    if (!flag_out || (L > 0 && (!perm || !marks))) return FEDRAG_ERR_NULL;
+    if ((reinterpret_cast<uintptr_t>(perm) | reinterpret_cast<uintptr_t>(marks) |
+         reinterpret_cast<uintptr_t>(flag_out)) & 3u)
+        return FEDRAG_ERR_ALIAS;
+    const size_t nb = (size_t)n_perm * (size_t)L * 4;
+    if (overlaps(perm, nb, marks, nb) || overlaps(flag_out, 4, marks, nb) || overlaps(flag_out, 4, perm, nb))
+        return FEDRAG_ERR_ALIAS;
+    return dev(launch_validate_perm(perm, n_perm, L, marks, flag_out, (hipStream_t)stream));
+}
+
 const char* fedrag_status_string(fedrag_status status) {
     switch (status) {
         case FEDRAG_OK: return "ok";

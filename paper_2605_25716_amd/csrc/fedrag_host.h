@@ -8,6 +8,9 @@
 
 namespace fedrag {
 
+// A launch grid's x dimension: the launchers refuse (hipErrorInvalidValue) what would not fit instead of truncating.
+inline bool grid_fits(int64_t n) { return n >= 1 && n <= 0x7fffffffLL; }
+
 // Second partial for the scatter form (Dec followed by the Section 4.1 aggregation of two partials): row i of X has
 // log-sum-exp lse_in[bh, i]; (O_other, lse_other) is the other partial, already in destination row order.
 struct RowsMerge {
@@ -43,6 +46,10 @@ struct RowsJob {
 };
 hipError_t launch_rows_transform(const RowsJob& job, hipStream_t stream);
 hipError_t launch_invert_perm(const int32_t* perm, int64_t L, int32_t* inv, hipStream_t stream);
+// flag[0] = 0 if every row of perm [n_perm, L] is a permutation of 0..L-1, else bit 0 (index out of range) and / or
+// bit 1 (index repeated); marks [n_perm, L] is scratch.
+hipError_t launch_validate_perm(const int32_t* perm, int n_perm, int64_t L, int32_t* marks, int32_t* flag,
+                                hipStream_t stream);
 
 // Partial attention problem: one KV shard (K, V, Lkv), or - n_shards > 1 - the shards a Compute Node holds for
 // the same queries, (Ks[i], Vs[i], Ls[i]), whose partials are aggregated inside the call.

@@ -60,6 +60,7 @@ hipError_t launch_lse_merge(const float* O_parts, const float* lses, int S, int6
     if (rows == 0) return hipSuccess;
     if (q_lens && (Lq < 1 || rows_per_seq < 1)) return hipErrorInvalidValue;
     const int64_t threads = rows * (D / 4);
+    if (!grid_fits((threads + 255) / 256)) return hipErrorInvalidValue;
     const dim3 grid((unsigned)((threads + 255) / 256));
     if (D == 128)
         hipLaunchKernelGGL(lse_merge_kernel<128>, grid, dim3(256), 0, stream, O_parts, lses, S, rows, O, lse,
@@ -73,6 +74,7 @@ hipError_t launch_lse_merge(const float* O_parts, const float* lses, int S, int6
 hipError_t launch_fill_empty(float* O, float* lse, int64_t rows, int D, hipStream_t stream) {
     if (rows == 0) return hipSuccess;
     const int64_t threads = rows * (D / 4);
+    if (!grid_fits((threads + 255) / 256)) return hipErrorInvalidValue;
     const dim3 grid((unsigned)((threads + 255) / 256));
     if (D == 128)
         hipLaunchKernelGGL(fill_empty_kernel<128>, grid, dim3(256), 0, stream, O, lse, rows);
@@ -96,6 +98,7 @@ hipError_t launch_scatter_rows_f32(const float* in, const int32_t* perm, int64_t
                                    hipStream_t stream) {
     const int64_t total = n_bh * L;
     if (total == 0) return hipSuccess;
+    if (!grid_fits((total + 255) / 256)) return hipErrorInvalidValue;
     hipLaunchKernelGGL(scatter_rows_f32_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, in, perm,
                        L, total, out);
     return hipGetLastError();

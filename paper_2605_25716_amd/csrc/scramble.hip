@@ -601,6 +601,24 @@ __global__ void invert_perm_kernel(const int32_t* __restrict__ perm, int64_t L, 
     if (j < L) inv[perm[j]] = (int32_t)j;
 }
 
+// Debug aid: is every row of perm [n_perm, L] a permutation of 0..L-1?  marks [n_perm, L] counts the hits of every
+// index; flag receives bit 0 for an index outside [0, L) and bit 1 for an index that occurs more than once (every
+// index in range and none twice means all L occur).
+__global__ void validate_perm_clear_kernel(int32_t* __restrict__ marks, int64_t total, int32_t* __restrict__ flag) {
+    const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e < total) marks[e] = 0;
+    if (e == 0) flag[0] = 0;
+}
+__global__ void validate_perm_kernel(const int32_t* __restrict__ perm, int64_t L, int64_t total,
+                                     int32_t* __restrict__ marks, int32_t* __restrict__ flag) {
+    const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= total) return;
+    const int64_t row = e / L;
+    const int32_t p = perm[e];
+    if (p < 0 || p >= L) atomicOr(flag, 1);
+    else if (atomicAdd(&marks[row * L + p], 1) != 0) atomicOr(flag, 2);
+}
+
 // ------------------------------------------------------------------------------------------------ launchers
 static int ceil_div_i64(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
 
@@ -611,6 +629,7 @@ static ScrambleJob device_job(const RowsJob& j, int i) {
 template <class T, int D>
 static hipError_t launch_scramble16(const RowsJob& j, hipStream_t stream) {
     if (j.L <= kFewRows && j.quant_bits == 0) {
+        if (!grid_fits(j.BH)) return hipErrorInvalidValue;
         dim3 grid((unsigned)j.BH, (unsigned)j.n_jobs);
         const ScrambleJob a = device_job(j, 0), b = device_job(j, 1);
         if (j.structured)
@@ -662,6 +681,7 @@ static hipError_t launch_rows_mfma_f32(const RowsJob& j, hipStream_t stream) {
     if (spw < 1) spw = 1;
     if (spw > 64) spw = 64;
     const int chunks = ceil_div_i64(steps, spw);
+    if (!grid_fits(j.BH * chunks)) return hipErrorInvalidValue;
     dim3 grid((unsigned)(j.BH * chunks), (unsigned)j.n_jobs);
     const ScrambleJob a = device_job(j, 0), b = device_job(j, 1);
     if (j.structured)
@@ -683,6 +703,7 @@ static hipError_t launch_rows_f32(const RowsJob& j, hipStream_t stream) {
     if (tpw < 1) tpw = 1;
     if (tpw > 64) tpw = 64;
     const int chunks = ceil_div_i64(tiles, tpw);
+    if (!grid_fits(j.BH * chunks)) return hipErrorInvalidValue;
     dim3 grid((unsigned)(j.BH * chunks), (unsigned)j.n_jobs);
     const ScrambleJob a = device_job(j, 0), b = device_job(j, 1);
     if (j.structured)
@@ -713,6 +734,18 @@ hipError_t launch_rows_transform(const RowsJob& j, hipStream_t stream) {
 hipError_t launch_invert_perm(const int32_t* perm, int64_t L, int32_t* inv, hipStream_t stream) {
     if (L == 0) return hipSuccess;
     hipLaunchKernelGGL(invert_perm_kernel, dim3((unsigned)((L + 255) / 256)), dim3(256), 0, stream, perm, L, inv);
+    return hipGetLastError();
+}
+
+hipError_t launch_validate_perm(const int32_t* perm, int n_perm, int64_t L, int32_t* marks, int32_t* flag,
+                                hipStream_t stream) {
+    const int64_t total = (int64_t)n_perm * L;
+    if (!grid_fits((total > 0 ? total + 255 : 256) / 256)) return hipErrorInvalidValue;
+    const dim3 grid((unsigned)((total > 0 ? total + 255 : 256) / 256));
+    hipLaunchKernelGGL(validate_perm_clear_kernel, grid, dim3(256), 0, stream, marks, total, flag);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || total == 0) return e;
+    hipLaunchKernelGGL(validate_perm_kernel, grid, dim3(256), 0, stream, perm, L, total, marks, flag);
     return hipGetLastError();
 }
 

@@ -4,6 +4,7 @@ dereferenced pointers are safe here: each call below must fail validation)."""
 import ctypes
 import os
 import re
+import subprocess
 
 import pytest
 
@@ -390,6 +391,19 @@ def test_header_is_plain_c_and_links(tmp_path):
     r = subprocess.run([exe], capture_output=True, text=True, timeout=300)
     assert r.returncode == 0, f"exit {r.returncode}: {r.stdout} {r.stderr}"
     assert "abi ok" in r.stdout
+
+
+def test_host_paths_under_address_and_undefined_behaviour_sanitizers():
+    """The host side of every entry point (argument checks, key-run planner over 20000 random shapes, workspace
+    queries) with the library's host code built under ASan + UBSan; the C driver makes no call that could reach a
+    kernel launch, so this runs without a GPU.  A sanitizer report ends the program with a non-zero status."""
+    from paper_2605_25716_amd import build as fbuild
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    exe = fbuild.build_host_check(os.path.join(root, "tests", "c", "host_paths.c"))
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=0:abort_on_error=0", UBSAN_OPTIONS="print_stacktrace=1")
+    res = subprocess.run([exe], capture_output=True, text=True, env=env, timeout=300)
+    assert res.returncode == 0, f"host_paths under sanitizers failed:\n{res.stdout[-3000:]}\n{res.stderr[-3000:]}"
+    assert "host paths ok" in res.stdout
 
 
 def test_missing_library_fails_loudly(tmp_path):

@@ -85,3 +85,28 @@ def test_zero_sequences():
     out = fb.fedrag_unscramble(torch.zeros((0, Hq, 3, d), device=DEV), phi("phi_v_inv"), None)
     assert out.shape == (0, Hq, 3, d)
     torch.cuda.synchronize()
+
+
+def test_validate_perm_flags():
+    """The debug check of a token permutation: 0 for permutations, bit 0 for an index out of range, bit 1 for a repeat."""
+    L = 5000
+    g = torch.Generator().manual_seed(11)
+    good = torch.stack([torch.randperm(L, generator=g) for _ in range(3)]).to(torch.int32)
+    cases = {"good": (good, 0)}
+    bad = good.clone(); bad[1, 17] = L
+    cases["too_large"] = (bad, 1)
+    bad = good.clone(); bad[2, 0] = -1
+    cases["negative"] = (bad, 1)
+    bad = good.clone(); bad[0, 5] = bad[0, 6]
+    cases["repeat"] = (bad, 2)
+    bad = good.clone(); bad[0, 5] = bad[0, 6]; bad[2, 9] = L + 3
+    cases["both"] = (bad, 3)
+    cases["one_row"] = (good[0].contiguous(), 0)
+    # a row that is a permutation of another row's range only as a whole tensor: rows are checked one by one
+    two = torch.stack([torch.arange(4), torch.tensor([0, 1, 2, 2])]).to(torch.int32)
+    cases["second_row_repeats"] = (two, 2)
+    for name, (perm, want) in cases.items():
+        flag = fb.fedrag_validate_perm(perm.to(DEV))
+        torch.cuda.synchronize()
+        assert int(flag.item()) == want, name
+    assert int(fb.fedrag_validate_perm(torch.zeros((1, 0), dtype=torch.int32, device=DEV)).item()) == 0
