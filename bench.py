@@ -4,8 +4,11 @@
 A step is one pass of all five calls over the Llama-3-8B-shaped decode workload (batch 16, 32 query / 8 KV
 heads, d 128, 4 shards of 8192 tokens, bf16): scramble_q, then per shard scramble_kv and partial_attn, then
 lse_merge and unscramble.  `value` is the step's algorithmic HBM bytes divided by the step time.  The same
-JSON line carries the roofline of the kernel that dominates the step, per-call figures, the RAG-prefill
-TFLOP/s (2048 queries x 16384 keys) and the CPU oracle timed on a bounded sample of the same workload.
+JSON line carries the roofline of the kernel that dominates the step (`roofline`) and of the two attention kernels
+a target is stated for (`rooflines`), per-call figures, what a plain copy and a bare MFMA loop reach on the device in
+the same run (`achievable`), one leg per other configuration (RAG prefill, long-context decode, the 70B-shaped mixed
+batch, request-sized chains, re-ranking, codec, structured keys; medians of at least 20 iterations) and the CPU
+oracle timed on the host cores: on the whole step, and on the other configurations in full or on a scaled sample.
 
     python bench.py --gpus 1 --steps 20 --warmup 3
 """
@@ -22,12 +25,15 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16 MFMA
 
-# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by a 1 GiB copy kernel of
-# known size; see profiles/bench_llama8b_decode_hbm_traffic.txt for the commands and the readings).
+# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a 1 GiB copy kernel of known size.
+# Counters cannot be read from inside this program: the figures are those of the named profile, which was taken
+# with this file's own command line, and they go stale when the kernel changes (re-run the profile then).
+TRAFFIC_PROFILE = "profiles/bench_llama8b_decode_hbm_traffic.txt"
 MEASURED_TRAFFIC_BYTES = {
     "scramble_kv": int((516.46 + 512.02) * 2**20),
     "partial_attn": int((512.48 + 0.51) * 2**20),
 }
+MIN_ITERS = 20   # timed iterations of every extra leg (medians are reported beside the means)
 
 
 def parse():
@@ -39,8 +45,9 @@ def parse():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replay of the step")
     ap.add_argument("--legs", default="all",
-                    help="comma-separated extra legs to run after the decode step: shards, codec, structured, rerank, "
-                         "local_attn, request, mixed70b, prefill, long_decode (default: all; 'none' for the step alone)")
+                    help="comma-separated extra legs to run after the decode step: achievable, shards, codec, structured, "
+                         "rerank, local_attn, request, mixed70b, prefill, long_decode (default: all; 'none' for the "
+                         "step alone)")
     ap.add_argument("--cpu-shards", type=int, default=4, help="KV shards (all sequences) the oracle is timed on")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run one 1 GiB device-to-device copy kernel before the timed region: a kernel of known "
@@ -67,9 +74,24 @@ class CallTimer:
     def summary(self):
         out = {}
         for name, pairs in self.pairs.items():
-            ms = [a.elapsed_time(b) for a, b in pairs]
-            out[name] = {"calls": len(ms), "avg_us": 1e3 * sum(ms) / len(ms), "total_ms": sum(ms)}
+            ms = sorted(a.elapsed_time(b) for a, b in pairs)
+            out[name] = {"calls": len(ms), "avg_us": 1e3 * sum(ms) / len(ms), "total_ms": sum(ms),
+                         "med_us": 1e3 * (ms[len(ms) // 2] + ms[(len(ms) - 1) // 2]) / 2}
         return out
+
+
+def measure(torch, fn, iters, warmup):
+    """`warmup` untimed calls of fn, then `iters` calls each between its own pair of HIP events on the current
+    stream.  Returns {"avg_us", "med_us", "iters"}."""
+    for _ in range(max(1, warmup)):
+        fn()
+    torch.cuda.synchronize()
+    timer = CallTimer(torch)
+    for _ in range(iters):
+        timer.run("x", fn)
+    torch.cuda.synchronize()
+    t = timer.summary()["x"]
+    return {"avg_us": t["avg_us"], "med_us": t["med_us"], "iters": iters}
 
 
 def decode_workload(torch, W, fb, dev):
@@ -162,18 +184,13 @@ def shards_leg(torch, fb, g, steps, warmup):
     ws = torch.empty(max(need, 16), dtype=torch.uint8, device=g["Qs"].device)
     O, lse = torch.empty_like(g["O"]), torch.empty_like(g["lse"])
     call = lambda: fb.fedrag_partial_attn_shards(g["Qs"], g["Ks"], g["Vs"], None, O=O, lse=lse, workspace=ws)
-    for _ in range(warmup):
-        call()
-    torch.cuda.synchronize()
-    timer = CallTimer(torch)
-    for _ in range(steps):
-        timer.run("a", call)
-    torch.cuda.synchronize()
-    us = timer.summary()["a"]["avg_us"]
+    t = measure(torch, call, max(steps, MIN_ITERS), warmup)
+    us = t["med_us"]
     nb = cfg.n_shards * g["bytes"]["partial_attn"]
     # the aggregation adds the partials in another order than per shard + across shards: equal to rounding
     err = float((O - g["O"]).abs().max())
-    return {"call": "partial_attn_shards (4 shards + aggregation)", "avg_us": round(us, 2), "bytes": nb,
+    return {"call": "partial_attn_shards (4 shards + aggregation)", "med_us": round(us, 2),
+            "avg_us": round(t["avg_us"], 2), "iters": t["iters"], "bytes": nb,
             "GB/s": round(nb / us / 1e3, 1), "frac_hbm": round(nb / us / 1e3 / HBM_PEAK_GBS, 4),
             "max_abs_diff_vs_step": err}
 
@@ -187,47 +204,45 @@ def structured_leg(torch, W, fb, g, dev, steps, warmup):
     perm = ks.perm_kv[0].to(dev)
     call = lambda: fb.fedrag_scramble_kv_structured(g["K"][0], g["V"][0], kk, kv, perm, n_q_heads=cfg.n_q_heads,
                                                     K_out=g["Ks"][0], V_out=g["Vs"][0])
-    for _ in range(warmup):
-        call()
-    torch.cuda.synchronize()
-    timer = CallTimer(torch)
-    for _ in range(steps):
-        timer.run("scramble_kv_structured", call)
-    torch.cuda.synchronize()
-    t = timer.summary()["scramble_kv_structured"]
-    gbs = g["bytes"]["scramble_kv"] / (t["avg_us"] * 1e-6) / 1e9
-    return {"call": "scramble_kv_structured", "avg_us": round(t["avg_us"], 2), "bytes": g["bytes"]["scramble_kv"],
-            "GB/s": round(gbs, 1), "frac_hbm": round(gbs / HBM_PEAK_GBS, 4)}
+    t = measure(torch, call, max(steps, MIN_ITERS), warmup)
+    gbs = g["bytes"]["scramble_kv"] / (t["med_us"] * 1e-6) / 1e9
+    return {"call": "scramble_kv_structured", "med_us": round(t["med_us"], 2), "avg_us": round(t["avg_us"], 2),
+            "iters": t["iters"], "bytes": g["bytes"]["scramble_kv"], "GB/s": round(gbs, 1),
+            "frac_hbm": round(gbs / HBM_PEAK_GBS, 4)}
 
 
 def local_attn_leg(torch, W, fb, dev, steps, warmup):
-    """The Inquirer's own part of a segment's attention: 4096 plaintext tokens attending to themselves and their
-    predecessors, Llama-3-8B head shape.  Counted flops: 4 d Hq Lq (Lq + 1) / 2 (visible pairs only)."""
-    B, Hq, Hkv, d, L = 1, 32, 8, 128, 4096
+    """The Inquirer's own part of a segment's attention: plaintext tokens attending to themselves and their
+    predecessors, Llama-3-8B head shape, segments of 2048 and 4096 tokens.  Counted flops: 4 d Hq Lq (Lq + 1) / 2
+    (visible pairs only).  The kernel feeds the second product two storage-type terms per probability (plaintext V
+    keeps its outlier channels), i.e. 1.5 x the matrix work of the counted flops."""
+    B, Hq, Hkv, d = 1, 32, 8, 128
     dt = torch.bfloat16
-    mk = lambda H, tid: W.activations(B, H, L, d, seed=W.BASE_SEED + 6, tensor_id=tid, outliers=True, outlier_id=tid,
-                                      dtype=dt, device=dev)
-    Q, K, V = mk(Hq, W.TID_Q), mk(Hkv, W.TID_K), mk(Hkv, W.TID_V)
-    O = torch.empty((B, Hq, L, d), dtype=torch.float32, device=dev)
-    lse = torch.empty((B, Hq, L), dtype=torch.float32, device=dev)
-    for _ in range(warmup):
-        fb.fedrag_local_attn(Q, K, V, None, O_part=O, lse=lse)
-    torch.cuda.synchronize()
-    timer = CallTimer(torch)
-    for _ in range(steps):
-        timer.run("local_attn", lambda: fb.fedrag_local_attn(Q, K, V, None, O_part=O, lse=lse))
-    torch.cuda.synchronize()
-    t = timer.summary()["local_attn"]
-    flop = 4.0 * d * Hq * B * (L * (L + 1) / 2)
-    tflops = flop / (t["avg_us"] * 1e-6) / 1e12
-    return {"workload": "local_attn: B1 Hq32 Hkv8 d128, 4096-token segment, bf16", "flop": flop,
-            "avg_us": round(t["avg_us"], 2), "value": round(tflops, 1), "unit": "TFLOP/s",
-            "frac_mfma": round(tflops / MFMA_BF16_PEAK_TFLOPS, 4)}
+    out = {"workload": "local_attn: B1 Hq32 Hkv8 d128 bf16, whole segment attends to itself (causal), plaintext "
+                       "Q, K, V with outlier channels"}
+    for L in (2048, 4096):
+        mk = lambda H, tid: W.activations(B, H, L, d, seed=W.BASE_SEED + 6, tensor_id=tid, outliers=True,
+                                          outlier_id=tid, dtype=dt, device=dev)
+        Q, K, V = mk(Hq, W.TID_Q), mk(Hkv, W.TID_K), mk(Hkv, W.TID_V)
+        O = torch.empty((B, Hq, L, d), dtype=torch.float32, device=dev)
+        lse = torch.empty((B, Hq, L), dtype=torch.float32, device=dev)
+        need = fb.fedrag_local_attn_workspace_bytes(B, Hq, Hkv, d, dt, L, L) \
+            if hasattr(fb, "fedrag_local_attn_workspace_bytes") else 0
+        ws = torch.empty(max(need, 16), dtype=torch.uint8, device=dev)
+        t = measure(torch, lambda: fb.fedrag_local_attn(Q, K, V, None, O_part=O, lse=lse, workspace=ws),
+                    max(steps, MIN_ITERS), warmup)
+        flop = 4.0 * d * Hq * B * (L * (L + 1) / 2)
+        tflops = flop / (t["med_us"] * 1e-6) / 1e12
+        out[f"segment_{L}"] = {"flop": flop, "med_us": round(t["med_us"], 2), "avg_us": round(t["avg_us"], 2),
+                               "iters": t["iters"], "value": round(tflops, 1), "unit": "TFLOP/s",
+                               "frac_mfma": round(tflops / MFMA_BF16_PEAK_TFLOPS, 4)}
+    return out
 
 
 def rerank_leg(torch, W, fb, dev, steps, warmup):
     """Re-ranking shape (Section 7.1: 10 candidate documents): 10 query-document pairs of unequal length, 16 heads of
-    64 channels, bidirectional attention of every token of a pair over the pair, padded to 1024 tokens."""
+    64 channels, bidirectional attention of every token of a pair over the pair, padded to 1024 tokens; on 16-bit
+    K', V' and on their 4-bit transport codes (Section 7.5 recommends 4 bits for re-ranking)."""
     B, H, d, Lmax = 10, 16, 64, 1024
     lens = [1024, 896, 777, 640, 512, 512, 400, 333, 256, 130]
     dt = torch.bfloat16
@@ -240,38 +255,64 @@ def rerank_leg(torch, W, fb, dev, steps, warmup):
     O = torch.empty((B, H, Lmax, d), dtype=torch.float32, device=dev)
     lse = torch.empty((B, H, Lmax), dtype=torch.float32, device=dev)
     call = lambda: fb.fedrag_partial_attn_varlen(Qs, Ks, Vs, kv, None, O_part=O, lse=lse, q_lens=kv)
-    for _ in range(warmup):
-        call()
-    torch.cuda.synchronize()
-    timer = CallTimer(torch)
-    for _ in range(steps):
-        timer.run("rerank", call)
-    torch.cuda.synchronize()
-    t = timer.summary()["rerank"]
+    t = measure(torch, call, max(steps, MIN_ITERS), warmup)
     flop = sum(4.0 * n * n * d * H for n in lens)   # real pairs only: n queries x n keys
-    return {"workload": "rerank: 10 pairs of 130..1024 tokens padded to 1024, 16 heads x 64, bf16, bidirectional",
-            "flop_valid_pairs": flop, "avg_us": round(t["avg_us"], 2),
-            "value": round(flop / (t["avg_us"] * 1e-6) / 1e12, 1), "unit": "TFLOP/s"}
+    out = {"workload": "rerank: 10 pairs of 130..1024 tokens padded to 1024, 16 heads x 64, bf16, bidirectional",
+           "flop_valid_pairs": flop, "med_us": round(t["med_us"], 2), "avg_us": round(t["avg_us"], 2),
+           "iters": t["iters"], "value": round(flop / (t["med_us"] * 1e-6) / 1e12, 1), "unit": "TFLOP/s"}
+    if hasattr(fb, "fedrag_partial_attn_varlen_quantized"):
+        for bits in (8, 4):
+            Kc, Kp = fb.fedrag_quantize_rows(Ks, bits)
+            Vc, Vp = fb.fedrag_quantize_rows(Vs, bits)
+            O2, l2 = torch.empty_like(O), torch.empty_like(lse)
+            callq = lambda: fb.fedrag_partial_attn_varlen_quantized(Qs, Kc, Kp, Vc, Vp, bits, kv, None, O_part=O2,
+                                                                    lse=l2, q_lens=kv)
+            tq = measure(torch, callq, max(steps, MIN_ITERS), warmup)
+            out[f"on_{bits}bit_codes"] = {"med_us": round(tq["med_us"], 2), "avg_us": round(tq["avg_us"], 2),
+                                          "value": round(flop / (tq["med_us"] * 1e-6) / 1e12, 1), "unit": "TFLOP/s"}
+    return out
 
 
 def mixed_leg(torch, W, fb, dev, steps, warmup):
-    """70B-shaped mixed batch (64 query heads over 8 KV heads, 8 shards x 8192 tokens): 32 decoding sequences and one
-    4096-token prefill chunk.  partial_attn over the 8 shards + lse_merge for each part, alone and with the two parts
-    issued on two streams at once (scramble_kv is timed on its own in the main step)."""
+    """70B-shaped mixed batch (64 query heads over 8 KV heads, 8 shards x 8192 tokens, 33 sequences): 32 decoding
+    sequences and one 4096-token prefill chunk.  Enc of one shard at this shape (all 33 sequences in one call);
+    partial_attn over the 8 shards + lse_merge for each part, shard by shard and as one call, alone and with the two
+    parts issued on two streams at once.  Inputs: the seeded generator with outlier channels, scrambled on the GPU."""
     cd, cp = W.CONFIGS["mixed70b_decode"], W.CONFIGS["mixed70b_prefill"]
     dt = W.torch_dtype(cd.dtype)
-    S, d = cd.n_shards, cd.d_head
-    gen = torch.Generator(device=dev)
-    gen.manual_seed(cd.seed)
-    rnd = lambda *shape: torch.randn(shape, generator=gen, device=dev).to(dt)
+    S, d, Hkv, L = cd.n_shards, cd.d_head, cd.n_kv_heads, cd.L_kv
+    Bd, Bp = cd.batch, cp.batch
+    Ball = Bd + Bp
+    iters = max(steps, MIN_ITERS)
+    keys = W.make_keys(Hkv, d, cp.L_q, L, S, seed=cd.seed, dtype=dt)
+    phi_k, phi_v, phi_q = keys.phi_k.to(dev), keys.phi_v.to(dev), keys.phi_q.to(dev)
+    act = lambda B, H, n, tid, oid: W.activations(B, H, n, d, seed=cd.seed, tensor_id=tid, outliers=True,
+                                                  outlier_id=oid, dtype=dt, device=dev)
+    Ks, Vs = [], []
+    enc = None
+    for s_ in range(S):
+        K, V = act(Ball, Hkv, L, W.TID_K + s_, W.TID_K), act(Ball, Hkv, L, W.TID_V + s_, W.TID_V)
+        perm = keys.perm_kv[s_].to(dev)
+        Ko, Vo = torch.empty_like(K), torch.empty_like(V)
+        call = lambda: fb.fedrag_scramble_kv(K, V, phi_k, phi_v, perm, n_q_heads=cd.n_q_heads, K_out=Ko, V_out=Vo)
+        if s_ == 0:   # Enc of one shard at this configuration's own shape, timed on its own
+            enc = measure(torch, call, iters, warmup)
+        else:
+            call()
+        Ks.append(Ko)
+        Vs.append(Vo)
+        torch.cuda.synchronize()
+        del K, V
+    enc_bytes = 8.0 * d * Ball * Hkv * L + 4 * L
+    Qd = fb.fedrag_scramble_q(act(Bd, cd.n_q_heads, 1, W.TID_Q, W.TID_Q), phi_q, None)
+    Qp = fb.fedrag_scramble_q(act(Bp, cp.n_q_heads, cp.L_q, W.TID_Q + 1, W.TID_Q), phi_q, keys.perm_q.to(dev))
 
-    def part(cfg):
-        Q = rnd(cfg.batch, cfg.n_q_heads, cfg.L_q, d)
-        KV = [(rnd(cfg.batch, cfg.n_kv_heads, cfg.L_kv, d), rnd(cfg.batch, cfg.n_kv_heads, cfg.L_kv, d))
-              for _ in range(S)]
+    def part(cfg, Q, lo, hi):
+        KV = [(Ks[s_][lo:hi], Vs[s_][lo:hi]) for s_ in range(S)]   # the part's sequences: a contiguous slab
         O = torch.empty((S, cfg.batch, cfg.n_q_heads, cfg.L_q, d), dtype=torch.float32, device=dev)
         lse = torch.empty((S, cfg.batch, cfg.n_q_heads, cfg.L_q), dtype=torch.float32, device=dev)
         Om, lm = torch.empty_like(O[0]), torch.empty_like(lse[0])
+        O1, l1 = torch.empty_like(O[0]), torch.empty_like(lse[0])
         need = fb.fedrag_partial_attn_workspace_bytes(cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, d, dt, cfg.L_q, cfg.L_kv)
         ws = torch.empty(max(need, 16), dtype=torch.uint8, device=dev)
 
@@ -284,45 +325,49 @@ def mixed_leg(torch, W, fb, dev, steps, warmup):
         ws1 = torch.empty(max(need1, 16), dtype=torch.uint8, device=dev)
 
         def run_one_call():
-            fb.fedrag_partial_attn_shards(Q, [kv[0] for kv in KV], [kv[1] for kv in KV], None, O=Om, lse=lm,
+            fb.fedrag_partial_attn_shards(Q, [kv[0] for kv in KV], [kv[1] for kv in KV], None, O=O1, lse=l1,
                                           workspace=ws1)
-        return run, run_one_call
+        diff = lambda: (float((Om - O1).abs().max()), float((lm - l1).abs().max()))
+        return run, run_one_call, diff
 
-    (run_d, run_d1), (run_p, run_p1) = part(cd), part(cp)
+    (run_d, run_d1, diff_d), (run_p, run_p1, diff_p) = part(cd, Qd, 0, Bd), part(cp, Qp, Bd, Ball)
     s_d, s_p = torch.cuda.Stream(), torch.cuda.Stream()   # default priority, both
 
-    def timed(fn):
-        for _ in range(warmup):
-            fn()
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(steps):
-            fn()
-        torch.cuda.synchronize()
-        return 1e3 * (time.perf_counter() - t0) / steps
-
     def both():
+        cur = torch.cuda.current_stream()
+        s_p.wait_stream(cur)
+        s_d.wait_stream(cur)
         with torch.cuda.stream(s_p):
             run_p()
         with torch.cuda.stream(s_d):
             run_d()
+        cur.wait_stream(s_p)
+        cur.wait_stream(s_d)
 
-    ms_d, ms_p, ms_b = timed(run_d), timed(run_p), timed(both)
-    ms_d1, ms_p1 = timed(run_d1), timed(run_p1)
-    byts = 4.0 * d * cd.batch * cd.n_kv_heads * cd.L_kv * S              # K' + V', 16-bit, read once per KV head
-    flop = 4.0 * cp.L_q * cp.L_kv * S * d * cp.n_q_heads * cp.batch
-    return {"workload": "mixed70b: Hq64 Hkv8 d128, 8 shards x 8192 tokens, bf16; 32 decode sequences + one 4096-token "
-                        "prefill chunk; partial_attn x 8 + lse_merge per part",
-            "decode": {"ms": round(ms_d, 4), "GB/s": round(byts / ms_d / 1e6, 1),
-                       "frac_hbm": round(byts / ms_d / 1e6 / HBM_PEAK_GBS, 4)},
-            "prefill": {"ms": round(ms_p, 4), "TFLOP/s": round(flop / ms_p / 1e9, 1),
-                        "frac_mfma": round(flop / ms_p / 1e9 / MFMA_BF16_PEAK_TFLOPS, 4)},
-            "decode_one_call": {"ms": round(ms_d1, 4), "GB/s": round(byts / ms_d1 / 1e6, 1),
-                                "frac_hbm": round(byts / ms_d1 / 1e6 / HBM_PEAK_GBS, 4)},
-            "prefill_one_call": {"ms": round(ms_p1, 4), "TFLOP/s": round(flop / ms_p1 / 1e9, 1),
-                                 "frac_mfma": round(flop / ms_p1 / 1e9 / MFMA_BF16_PEAK_TFLOPS, 4)},
-            "both_on_two_streams_ms": round(ms_b, 4), "sum_ms": round(ms_d + ms_p, 4),
-            "max_ms": round(max(ms_d, ms_p), 4)}
+    t_d, t_p = measure(torch, run_d, iters, warmup), measure(torch, run_p, iters, warmup)
+    t_b = measure(torch, both, iters, warmup)
+    t_d1, t_p1 = measure(torch, run_d1, iters, warmup), measure(torch, run_p1, iters, warmup)
+    torch.cuda.synchronize()
+    dd, dp = diff_d(), diff_p()
+    byts = 4.0 * d * Bd * Hkv * L * S              # K' + V', 16-bit, read once per KV head
+    flop = 4.0 * cp.L_q * L * S * d * cp.n_q_heads * Bp
+    ms = lambda t: t["med_us"] / 1e3
+    hbm = lambda t: {"ms": round(ms(t), 4), "avg_ms": round(t["avg_us"] / 1e3, 4), "GB/s": round(byts / ms(t) / 1e6, 1),
+                     "frac_hbm": round(byts / ms(t) / 1e6 / HBM_PEAK_GBS, 4)}
+    mf = lambda t: {"ms": round(ms(t), 4), "avg_ms": round(t["avg_us"] / 1e3, 4),
+                    "TFLOP/s": round(flop / ms(t) / 1e9, 1),
+                    "frac_mfma": round(flop / ms(t) / 1e9 / MFMA_BF16_PEAK_TFLOPS, 4)}
+    return {"workload": "mixed70b: Hq64 Hkv8 d128, 8 shards x 8192 tokens, bf16, 33 sequences: 32 decoding + one "
+                        "4096-token prefill chunk; partial_attn x 8 + lse_merge per part; medians of "
+                        f"{iters} iterations",
+            "scramble_kv_one_shard": {"ms": round(ms(enc), 4), "avg_ms": round(enc["avg_us"] / 1e3, 4),
+                                      "bytes": enc_bytes, "GB/s": round(enc_bytes / ms(enc) / 1e6, 1),
+                                      "frac_hbm": round(enc_bytes / ms(enc) / 1e6 / HBM_PEAK_GBS, 4)},
+            "decode": hbm(t_d), "prefill": mf(t_p), "decode_one_call": hbm(t_d1), "prefill_one_call": mf(t_p1),
+            "max_abs_diff_one_call_vs_shard_by_shard": {"decode_O": dd[0], "decode_lse": dd[1],
+                                                        "prefill_O": dp[0], "prefill_lse": dp[1]},
+            "both_on_two_streams_ms": round(ms(t_b), 4), "sum_ms": round(ms(t_d) + ms(t_p), 4),
+            "max_ms": round(max(ms(t_d), ms(t_p)), 4)}
 
 
 def request_leg(torch, W, fb, dev, steps, warmup, n_layers=32):
@@ -334,19 +379,28 @@ def request_leg(torch, W, fb, dev, steps, warmup, n_layers=32):
     (partial_attn_shards, unscramble_merge: 4 calls per layer) and call by call (8 calls per layer)."""
     B, Hq, Hkv, d, S, Lc, Lseg, Lgen = 1, 32, 8, 128, 2, 4096, 128, 64
     dt = torch.bfloat16
-    gen = torch.Generator(device=dev)
-    gen.manual_seed(W.BASE_SEED + 9)
-    rnd = lambda *shape: torch.randn(shape, generator=gen, device=dev).to(dt)
+    tid = [1000]
+
+    def rnd(b, h, n, dd, kind=W.TID_K):   # plaintext from the seeded generator, outlier channels fixed per tensor kind
+        tid[0] += 1
+        return W.activations(b, h, n, dd, seed=W.BASE_SEED + 9, tensor_id=tid[0], outliers=True, outlier_id=kind,
+                             dtype=dt, device=dev)
     keys = W.make_keys(Hkv, d, Lseg, Lc, S, seed=W.BASE_SEED + 9, dtype=dt)
     phi_q, phi_vi = keys.phi_q.to(dev), keys.phi_v_inv.to(dev)
+    phi_k, phi_v = keys.phi_k.to(dev), keys.phi_v.to(dev)
+    perms = [p_.to(dev) for p_ in keys.perm_kv]
     # per layer: the scrambled caches the Compute Node holds (distinct memory per layer, 1 GiB in all)
-    Ks = [[rnd(B, Hkv, Lc, d) for _ in range(S)] for _ in range(n_layers)]
-    Vs = [[rnd(B, Hkv, Lc, d) for _ in range(S)] for _ in range(n_layers)]
+    Ks, Vs = [], []
+    for _ in range(n_layers):
+        enc = [fb.fedrag_scramble_kv(rnd(B, Hkv, Lc, d, W.TID_K), rnd(B, Hkv, Lc, d, W.TID_V), phi_k, phi_v, perms[s_],
+                                     n_q_heads=Hq) for s_ in range(S)]
+        Ks.append([e[0] for e in enc])
+        Vs.append([e[1] for e in enc])
 
     def chain(Lq, L_local, fused):
-        Q = rnd(B, Hq, Lq, d)
-        Kl = [rnd(B, Hkv, L_local, d) for _ in range(n_layers)]   # the Inquirer's own plaintext K, V per layer
-        Vl = [rnd(B, Hkv, L_local, d) for _ in range(n_layers)]
+        Q = rnd(B, Hq, Lq, d, W.TID_Q)
+        Kl = [rnd(B, Hkv, L_local, d, W.TID_K) for _ in range(n_layers)]   # the Inquirer's own plaintext K, V per layer
+        Vl = [rnd(B, Hkv, L_local, d, W.TID_V) for _ in range(n_layers)]
         perm_q = keys.perm_q.to(dev) if Lq == Lseg else None
         f32 = lambda *shape: torch.empty(shape, dtype=torch.float32, device=dev)
         Qs = torch.empty_like(Q)
@@ -392,14 +446,8 @@ def request_leg(torch, W, fb, dev, steps, warmup, n_layers=32):
                                      ("segment_prefill_call_by_call", Lseg, Lseg, False),
                                      ("decode_token_call_by_call", 1, Lseg + Lgen, False)):
         run, out = chain(Lq, L_local, fused)
-        for _ in range(max(1, warmup)):
-            run()
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(steps):
-            run()
-        torch.cuda.synchronize()
-        eager_ms = 1e3 * (time.perf_counter() - t0) / steps
+        steps = max(steps, MIN_ITERS)
+        eager_ms = measure(torch, run, steps, warmup)["med_us"] / 1e3
         ref = out.clone()
         graph = torch.cuda.CUDAGraph()
         side = torch.cuda.Stream()
@@ -413,11 +461,7 @@ def request_leg(torch, W, fb, dev, steps, warmup, n_layers=32):
         graph.replay()
         torch.cuda.synchronize()
         same = bool(torch.equal(out, ref))
-        t0 = time.perf_counter()
-        for _ in range(steps):
-            graph.replay()
-        torch.cuda.synchronize()
-        graph_ms = 1e3 * (time.perf_counter() - t0) / steps
+        graph_ms = measure(torch, graph.replay, steps, 1)["med_us"] / 1e3
         res[name] = {"eager_ms": round(eager_ms, 4), "graph_ms": round(graph_ms, 4),
                      "graph_us_per_layer": round(1e3 * graph_ms / n_layers, 2), "replay_equals_eager": same}
     res["decode_token"]["tokens_per_s_attention_path"] = round(1e3 / res["decode_token"]["graph_ms"], 1)
@@ -425,25 +469,42 @@ def request_leg(torch, W, fb, dev, steps, warmup, n_layers=32):
 
 
 def long_decode_leg(torch, W, fb, dev, steps, warmup):
-    """Long-context decode (B64, 32/8 heads, d128, 8 shards x 32768 tokens, bf16): rows a3 + a4 with all 64 GiB of
-    K', V' resident, as one call over the 8 shards and shard by shard."""
+    """Long-context decode (B64, 32/8 heads, d128, 8 shards x 32768 tokens, bf16): Enc of one shard at this size, then
+    rows a3 + a4 with all 64 GiB of K', V' resident, as one call over the 8 shards and shard by shard.  Inputs: the
+    seeded generator with outlier channels, scrambled on the GPU shard by shard."""
     cfg = W.CONFIGS["long_decode"]
     dt = W.torch_dtype(cfg.dtype)
     B, Hq, Hkv, d, S, L = cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.d_head, cfg.n_shards, cfg.L_kv
-    gen = torch.Generator(device=dev)
-    gen.manual_seed(cfg.seed)
-
-    def rnd(*shape):   # drawn in slabs so that the fp32 intermediate stays small
-        out = torch.empty(shape, dtype=dt, device=dev)
-        for b in range(shape[0]):
-            out[b] = torch.randn(shape[1:], generator=gen, device=dev).to(dt)
-        return out
-    Q = rnd(B, Hq, 1, d)
-    Ks = [rnd(B, Hkv, L, d) for _ in range(S)]
-    Vs = [rnd(B, Hkv, L, d) for _ in range(S)]
-    O, lse = torch.empty((B, Hq, 1, d), dtype=torch.float32, device=dev), torch.empty((B, Hq, 1), dtype=torch.float32, device=dev)
-    Op = torch.empty((S, B, Hq, 1, d), dtype=torch.float32, device=dev)
-    lp = torch.empty((S, B, Hq, 1), dtype=torch.float32, device=dev)
+    iters = max(steps, MIN_ITERS)
+    keys = W.make_keys(Hkv, d, 1, L, S, seed=cfg.seed, dtype=dt)
+    phi_k, phi_v = keys.phi_k.to(dev), keys.phi_v.to(dev)
+    act = lambda H, n, tid, oid: W.activations(B, H, n, d, seed=cfg.seed, tensor_id=tid, outliers=True,
+                                               outlier_id=oid, dtype=dt, device=dev)
+    out = {"workload": "long_decode: B64 Hq32 Hkv8 d128 Lq1, 8 shards x 32768 tokens, bf16 (64 GiB of K', V'); "
+                       f"medians of {iters} iterations"}
+    Ks, Vs = [], []
+    for s_ in range(S):
+        K, V = act(Hkv, L, W.TID_K + s_, W.TID_K), act(Hkv, L, W.TID_V + s_, W.TID_V)
+        perm = keys.perm_kv[s_].to(dev)
+        Ko, Vo = torch.empty_like(K), torch.empty_like(V)
+        enc = lambda: fb.fedrag_scramble_kv(K, V, phi_k, phi_v, perm, n_q_heads=Hq, K_out=Ko, V_out=Vo)
+        if s_ == 0:   # Enc of one shard at this size (8 GiB read, 8 GiB written)
+            t = measure(torch, enc, iters, 2)
+            enc_bytes = 8.0 * d * B * Hkv * L + 4 * L
+            ms = t["med_us"] / 1e3
+            out["scramble_kv_one_shard"] = {"ms": round(ms, 3), "avg_ms": round(t["avg_us"] / 1e3, 3),
+                                            "GB/s": round(enc_bytes / ms / 1e6, 1),
+                                            "frac_hbm": round(enc_bytes / ms / 1e6 / HBM_PEAK_GBS, 4)}
+        else:
+            enc()
+        Ks.append(Ko)
+        Vs.append(Vo)
+        torch.cuda.synchronize()
+        del K, V
+    Q = fb.fedrag_scramble_q(act(Hq, 1, W.TID_Q, W.TID_Q), keys.phi_q.to(dev), None)
+    f32 = lambda *shape: torch.empty(shape, dtype=torch.float32, device=dev)
+    O, lse, O2, lse2 = f32(B, Hq, 1, d), f32(B, Hq, 1), f32(B, Hq, 1, d), f32(B, Hq, 1)
+    Op, lp = f32(S, B, Hq, 1, d), f32(S, B, Hq, 1)
     need = fb.fedrag_partial_attn_shards_workspace_bytes(B, Hq, Hkv, d, dt, 1, [L] * S)
     ws = torch.empty(max(need, 16), dtype=torch.uint8, device=dev)
     need1 = fb.fedrag_partial_attn_workspace_bytes(B, Hq, Hkv, d, dt, 1, L)
@@ -455,37 +516,17 @@ def long_decode_leg(torch, W, fb, dev, steps, warmup):
     def per_shard():
         for s_ in range(S):
             fb.fedrag_partial_attn(Q, Ks[s_], Vs[s_], None, O_part=Op[s_], lse=lp[s_], workspace=ws1)
-        fb.fedrag_lse_merge(Op, lp, n_kv_heads=Hkv, O_out=O, lse_out=lse)
+        fb.fedrag_lse_merge(Op, lp, n_kv_heads=Hkv, O_out=O2, lse_out=lse2)
 
-    out = {"workload": "long_decode: B64 Hq32 Hkv8 d128 Lq1, 8 shards x 32768 tokens, bf16 (64 GiB of K', V')"}
-    # Enc of one shard at this size (8 GiB read, 8 GiB written), into a spare pair of buffers
-    keys = W.make_keys(Hkv, d, 1, L, 1, seed=cfg.seed, dtype=dt)
-    phi_k, phi_v, perm = keys.phi_k.to(dev), keys.phi_v.to(dev), keys.perm_kv[0].to(dev)
-    Ko, Vo = torch.empty_like(Ks[0]), torch.empty_like(Vs[0])
-    enc = lambda: fb.fedrag_scramble_kv(Ks[0], Vs[0], phi_k, phi_v, perm, n_q_heads=Hq, K_out=Ko, V_out=Vo)
-    enc()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(3):
-        enc()
-    torch.cuda.synchronize()
-    ms = 1e3 * (time.perf_counter() - t0) / 3
-    enc_bytes = 8.0 * d * B * Hkv * L
-    out["scramble_kv_one_shard"] = {"ms": round(ms, 3), "GB/s": round(enc_bytes / ms / 1e6, 1),
-                                    "frac_hbm": round(enc_bytes / ms / 1e6 / HBM_PEAK_GBS, 4)}
-    del Ko, Vo
     byts = 4.0 * d * B * Hkv * L * S
     for name, fn in (("one_call", one_call), ("shard_by_shard", per_shard)):
-        for _ in range(max(1, warmup // 2)):
-            fn()
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(steps):
-            fn()
-        torch.cuda.synchronize()
-        ms = 1e3 * (time.perf_counter() - t0) / steps
-        out[name] = {"ms": round(ms, 3), "GB/s": round(byts / ms / 1e6, 1),
+        t = measure(torch, fn, iters, max(1, warmup // 2))
+        ms = t["med_us"] / 1e3
+        out[name] = {"ms": round(ms, 3), "avg_ms": round(t["avg_us"] / 1e3, 3), "GB/s": round(byts / ms / 1e6, 1),
                      "frac_hbm": round(byts / ms / 1e6 / HBM_PEAK_GBS, 4)}
+    torch.cuda.synchronize()
+    out["max_abs_diff_one_call_vs_shard_by_shard"] = {"O": float((O - O2).abs().max()),
+                                                      "lse": float((lse - lse2).abs().max())}
     return out
 
 
@@ -500,57 +541,37 @@ def codec_leg(torch, fb, g, steps, warmup):
         Xh = torch.empty_like(X)
         q = lambda: fb.fedrag_quantize_rows(X, bits, codes=codes, params=params)
         dq = lambda: fb.fedrag_dequantize_rows(codes, params, bits, X.dtype, X_out=Xh)
-        for _ in range(warmup):
-            q(); dq()
-        torch.cuda.synchronize()
-        timer = CallTimer(torch)
-        for _ in range(steps):
-            timer.run("q", q)
-            timer.run("dq", dq)
-        torch.cuda.synchronize()
-        t = timer.summary()
+        steps = max(steps, MIN_ITERS)
+        tq, tdq = measure(torch, q, steps, warmup), measure(torch, dq, steps, warmup)
         nbytes = n * (d * 2 + d * bits // 8 + 8)
-        out[f"{bits}bit"] = {"quantize_us": round(t["q"]["avg_us"], 2), "dequantize_us": round(t["dq"]["avg_us"], 2),
-                             "bytes": nbytes, "quantize_GB/s": round(nbytes / t["q"]["avg_us"] / 1e3, 1),
-                             "dequantize_GB/s": round(nbytes / t["dq"]["avg_us"] / 1e3, 1)}
+        out[f"{bits}bit"] = {"quantize_us": round(tq["med_us"], 2), "dequantize_us": round(tdq["med_us"], 2),
+                             "bytes": nbytes, "quantize_GB/s": round(nbytes / tq["med_us"] / 1e3, 1),
+                             "dequantize_GB/s": round(nbytes / tdq["med_us"] / 1e3, 1)}
     # Enc with the codec as its epilogue (what a Context Owner sends): one shard, K and V
     cfg = g["cfg"]
     outs = fb.fedrag_scramble_kv_quantized(g["K"][0], g["V"][0], g["phi_k"], g["phi_v"], g["perm_kv"][0], 8,
                                            n_q_heads=cfg.n_q_heads)
     call = lambda: fb.fedrag_scramble_kv_quantized(g["K"][0], g["V"][0], g["phi_k"], g["phi_v"], g["perm_kv"][0], 8,
                                                    n_q_heads=cfg.n_q_heads, out=outs)
-    for _ in range(warmup):
-        call()
-    torch.cuda.synchronize()
-    timer = CallTimer(torch)
-    for _ in range(steps):
-        timer.run("f", call)
-    torch.cuda.synchronize()
-    us = timer.summary()["f"]["avg_us"]
+    us = measure(torch, call, steps, warmup)["med_us"]
     nb = 2 * n * (d * 2 + d + 8) + 4 * cfg.L_kv
-    out["scramble_kv_quantized_8bit"] = {"avg_us": round(us, 2), "bytes": nb, "GB/s": round(nb / us / 1e3, 1)}
+    out["scramble_kv_quantized_8bit"] = {"med_us": round(us, 2), "bytes": nb, "GB/s": round(nb / us / 1e3, 1)}
     # the Compute Node's decode call reading the codes directly (one shard)
     for bits in (8, 4):
         Kc, Kp, Vc, Vp = fb.fedrag_scramble_kv_quantized(g["K"][0], g["V"][0], g["phi_k"], g["phi_v"], g["perm_kv"][0],
                                                          bits, n_q_heads=cfg.n_q_heads)
         call = lambda: fb.fedrag_partial_attn_quantized(g["Qs"], Kc, Kp, Vc, Vp, bits, None, O_part=g["O_parts"][0],
                                                         lse=g["lses"][0], workspace=g["ws"])
-        for _ in range(warmup):
-            call()
-        torch.cuda.synchronize()
-        timer = CallTimer(torch)
-        for _ in range(steps):
-            timer.run("a", call)
-        torch.cuda.synchronize()
-        us = timer.summary()["a"]["avg_us"]
+        us = measure(torch, call, steps, warmup)["med_us"]
         nb = 2 * n * (d * bits // 8 + 8)
-        out[f"partial_attn_quantized_{bits}bit"] = {"avg_us": round(us, 2), "bytes_read": nb,
+        out[f"partial_attn_quantized_{bits}bit"] = {"med_us": round(us, 2), "bytes_read": nb,
                                                     "GB/s": round(nb / us / 1e3, 1)}
     return out
 
 
-def prefill_leg(torch, W, fb, dev, steps, warmup):
-    """RAG prefill: partial_attn alone, 2048 queries x 16384 keys, 32/8 heads, d 128, bf16."""
+def prefill_leg(torch, W, fb, dev, steps, warmup, keep=None):
+    """RAG prefill: partial_attn alone, 2048 queries x 16384 keys, 32/8 heads, d 128, bf16.  `keep`, a dict, receives
+    host copies of Q', K', V' for the oracle's timing leg."""
     cfg = W.CONFIGS["rag_prefill"]
     dt = W.torch_dtype(cfg.dtype)
     mk = lambda H, L, tid, oid: W.activations(cfg.batch, H, L, cfg.d_head, seed=cfg.seed, tensor_id=tid, outliers=True,
@@ -560,31 +581,69 @@ def prefill_leg(torch, W, fb, dev, steps, warmup):
     keys = W.make_keys(cfg.n_kv_heads, cfg.d_head, cfg.L_q, cfg.L_kv, 1, seed=cfg.seed, dtype=dt)
     Qs = fb.fedrag_scramble_q(Q, keys.phi_q.to(dev), keys.perm_q.to(dev))
     Ks, Vs = fb.fedrag_scramble_kv(K, V, keys.phi_k.to(dev), keys.phi_v.to(dev), keys.perm_kv[0].to(dev))
+    if keep is not None:
+        keep.update(Qs=Qs.cpu(), Ks=Ks.cpu(), Vs=Vs.cpu())
     O = torch.empty((cfg.batch, cfg.n_q_heads, cfg.L_q, cfg.d_head), dtype=torch.float32, device=dev)
     lse = torch.empty((cfg.batch, cfg.n_q_heads, cfg.L_q), dtype=torch.float32, device=dev)
-    for _ in range(warmup):
-        fb.fedrag_partial_attn(Qs, Ks, Vs, None, O_part=O, lse=lse)
-    torch.cuda.synchronize()
-    timer = CallTimer(torch)
-    for _ in range(steps):
-        timer.run("partial_attn", lambda: fb.fedrag_partial_attn(Qs, Ks, Vs, None, O_part=O, lse=lse))
-    torch.cuda.synchronize()
-    t = timer.summary()["partial_attn"]
+    iters = max(steps, MIN_ITERS)
+    t = measure(torch, lambda: fb.fedrag_partial_attn(Qs, Ks, Vs, None, O_part=O, lse=lse), iters, warmup)
     # the Inquirer's two calls around it at this size (a2 before, a5 after)
     phi_q, perm_q, phi_vi = keys.phi_q.to(dev), keys.perm_q.to(dev), keys.phi_v_inv.to(dev)
     out = torch.empty_like(O)
-    for _ in range(steps):
-        timer.run("scramble_q", lambda: fb.fedrag_scramble_q(Q, phi_q, perm_q, Q_out=Qs))
-        timer.run("unscramble", lambda: fb.fedrag_unscramble(O, phi_vi, perm_q, O_out=out))
-    torch.cuda.synchronize()
-    around = {k: round(v["avg_us"], 2) for k, v in timer.summary().items() if k != "partial_attn"}
+    Q2 = torch.empty_like(Qs)
+    around = {"scramble_q": round(measure(torch, lambda: fb.fedrag_scramble_q(Q, phi_q, perm_q, Q_out=Q2), iters, 2)["med_us"], 2),
+              "unscramble": round(measure(torch, lambda: fb.fedrag_unscramble(O, phi_vi, perm_q, O_out=out), iters, 2)["med_us"], 2)}
     flop = 4.0 * cfg.L_q * cfg.L_kv * cfg.d_head * cfg.n_q_heads * cfg.batch
     tflops = flop / (t["avg_us"] * 1e-6) / 1e12
     return {"workload": "rag_prefill: B1 Hq32 Hkv8 d128 Lq2048 Lkv16384 bf16, non-causal", "flop": flop,
-            "avg_us": t["avg_us"], "value": tflops, "unit": "TFLOP/s", "inquirer_calls_avg_us": around,
-            "roofline": {"bound": "mfma", "achieved": tflops, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                         "frac": tflops / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
-                         "kernel": "prefill_attn_kernel<BF16,128>"}}
+            "avg_us": round(t["avg_us"], 2), "med_us": round(t["med_us"], 2), "iters": iters,
+            "value": round(tflops, 1), "unit": "TFLOP/s",
+            "inquirer_calls_med_us": around,
+            "roofline": {"bound": "mfma", "achieved": round(tflops, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                         "frac": round(tflops / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
+                         "kernel": "prefill_attn_kernel<BF16,128,false>", "avg_us": round(t["avg_us"], 2),
+                         "flop_per_launch": flop}}
+
+
+def achievable_leg(torch, dev):
+    """What plain kernels reach on this device in this run, beside the published peaks the fractions are quoted
+    against: a streaming copy and a streaming read of 1 GiB (beyond the 256 MB last-level cache) and a bare bf16 MFMA
+    issue loop.  The kernels live in libfedrag_probes.so (csrc/probes/rate_probes.hip)."""
+    import ctypes
+    from paper_2605_25716_amd import build as fbuild
+    if not os.path.exists(fbuild.PROBES_LIB):
+        fbuild.build_probes(force=True)
+    lib = ctypes.CDLL(fbuild.PROBES_LIB)
+    vp = ctypes.c_void_p
+    lib.fedrag_probe_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
+    lib.fedrag_probe_read.argtypes = [vp, ctypes.c_size_t, vp, vp]
+    lib.fedrag_probe_mfma_bf16.argtypes = [vp, ctypes.c_int, vp]
+    lib.fedrag_probe_mfma_bf16_flop.argtypes = [ctypes.c_int]
+    lib.fedrag_probe_mfma_bf16_flop.restype = ctypes.c_double
+    n = 1 << 30
+    a = torch.empty(n, dtype=torch.uint8, device=dev)
+    b = torch.empty_like(a)
+    a.fill_(1)
+    sink = torch.zeros(4, dtype=torch.float32, device=dev)
+    stream = lambda: vp(torch.cuda.current_stream().cuda_stream)
+
+    def chk(rc):
+        if rc != 0:
+            raise RuntimeError(f"probe launch failed ({rc})")
+    tc = measure(torch, lambda: chk(lib.fedrag_probe_copy(b.data_ptr(), a.data_ptr(), n, stream())), MIN_ITERS, 3)
+    tr = measure(torch, lambda: chk(lib.fedrag_probe_read(a.data_ptr(), n, sink.data_ptr(), stream())), MIN_ITERS, 3)
+    iters = 4096
+    tm = measure(torch, lambda: chk(lib.fedrag_probe_mfma_bf16(sink.data_ptr(), iters, stream())), MIN_ITERS, 3)
+    flop = float(lib.fedrag_probe_mfma_bf16_flop(iters))
+    ok = bool(torch.equal(a, b))
+    del a, b
+    return {"copy_GB/s": round(2.0 * n / tc["med_us"] / 1e3, 1), "copy_frac_of_hbm_peak": round(2.0 * n / tc["med_us"] / 1e3 / HBM_PEAK_GBS, 4),
+            "read_GB/s": round(1.0 * n / tr["med_us"] / 1e3, 1), "read_frac_of_hbm_peak": round(1.0 * n / tr["med_us"] / 1e3 / HBM_PEAK_GBS, 4),
+            "mfma_bf16_TFLOP/s": round(flop / tm["med_us"] / 1e6, 1),
+            "mfma_frac_of_peak": round(flop / tm["med_us"] / 1e6 / MFMA_BF16_PEAK_TFLOPS, 4),
+            "copy_verified": ok,
+            "what": "medians of 20 launches: 1 GiB device copy (read + write bytes), 1 GiB streaming read, "
+                    "256 workgroups x 8 waves x 4096 x 8 independent 32x32x16 bf16 MFMAs on register operands"}
 
 
 def cpu_leg(torch, W, g, n_shards):
@@ -617,6 +676,63 @@ def cpu_leg(torch, W, g, n_shards):
             "seconds": round(dt, 3),
             "sample": f"KV shards 0..{n_shards - 1} of {cfg.n_shards}, all {cfg.batch} sequences: the whole step in fp64 "
                       f"({nbytes / 2**30:.2f} GiB of the step's {g['step_bytes'] / 2**30:.2f} GiB algorithmic bytes)"}
+
+
+def cpu_other_configs(torch, W, kept):
+    """The oracle (partial attention per shard + aggregation, fp64, its own thread pool) on the other configurations:
+    the RAG prefill in full; the long-context decode and the two parts of the 70B-shaped batch on a seeded sample of
+    (sequence, KV head) units of every shard, scaled linearly to the whole configuration (the work per unit is
+    uniform) and marked as extrapolated."""
+    import numpy as np
+    import oracle
+    out = {}
+    if kept:   # configuration 3, whole: the same Q', K', V' bits the GPU leg consumed
+        cfg = W.CONFIGS["rag_prefill"]
+        t0 = time.perf_counter()
+        oracle.partial_attn(kept["Qs"], kept["Ks"], kept["Vs"])
+        dt = time.perf_counter() - t0
+        flop = 4.0 * cfg.L_q * cfg.L_kv * cfg.d_head * cfg.n_q_heads * cfg.batch
+        out["rag_prefill"] = {"value": round(flop / dt / 1e12, 5), "unit": "TFLOP/s", "seconds": round(dt, 3),
+                              "extrapolated": False, "sample": "the whole configuration (2048 x 16384, 32 heads)"}
+
+    def sampled(cfg, n_units, q_rows):
+        dt_ = W.torch_dtype(cfg.dtype)
+        G, S, d = cfg.group, cfg.n_shards, cfg.d_head
+        act = lambda H, n, tid: W.activations(n_units, H, n, d, seed=cfg.seed + 77, tensor_id=tid, outliers=False, dtype=dt_)
+        Q = act(G, q_rows, W.TID_Q)                      # the sampled units as a batch of single-KV-head sequences
+        KV = [(act(1, cfg.L_kv, W.TID_K + s_), act(1, cfg.L_kv, W.TID_V + s_)) for s_ in range(S)]
+        t0 = time.perf_counter()
+        parts = [oracle.partial_attn(Q, k, v) for k, v in KV]
+        oracle.lse_merge(np.stack([p_[0] for p_ in parts]), np.stack([p_[1] for p_ in parts]))
+        return time.perf_counter() - t0
+
+    cfg = W.CONFIGS["long_decode"]
+    n = 8
+    dt = sampled(cfg, n, 1)
+    scale = cfg.batch * cfg.n_kv_heads / n
+    byts = 4.0 * cfg.d_head * cfg.batch * cfg.n_kv_heads * cfg.L_kv * cfg.n_shards
+    out["long_decode"] = {"value": round(byts / (dt * scale) / 1e9, 4), "unit": "GB/s", "seconds": round(dt, 3),
+                          "extrapolated": True, "seconds_whole_configuration": round(dt * scale, 1),
+                          "sample": f"{n} of {cfg.batch * cfg.n_kv_heads} (sequence, KV head) units of each of the "
+                                    f"{cfg.n_shards} shards, scaled by {scale:g}"}
+    cfg = W.CONFIGS["mixed70b_decode"]
+    dt = sampled(cfg, n, 1)
+    scale = cfg.batch * cfg.n_kv_heads / n
+    byts = 4.0 * cfg.d_head * cfg.batch * cfg.n_kv_heads * cfg.L_kv * cfg.n_shards
+    out["mixed70b_decode"] = {"value": round(byts / (dt * scale) / 1e9, 4), "unit": "GB/s", "seconds": round(dt, 3),
+                              "extrapolated": True, "seconds_whole_configuration": round(dt * scale, 1),
+                              "sample": f"{n} of {cfg.batch * cfg.n_kv_heads} units of each of the {cfg.n_shards} "
+                                        f"shards, scaled by {scale:g}"}
+    cfg = W.CONFIGS["mixed70b_prefill"]
+    rows = 32
+    dt = sampled(cfg, cfg.n_kv_heads, rows)
+    scale = cfg.L_q / rows
+    flop = 4.0 * cfg.L_q * cfg.L_kv * cfg.n_shards * cfg.d_head * cfg.n_q_heads * cfg.batch
+    out["mixed70b_prefill"] = {"value": round(flop / (dt * scale) / 1e12, 5), "unit": "TFLOP/s", "seconds": round(dt, 3),
+                               "extrapolated": True, "seconds_whole_configuration": round(dt * scale, 1),
+                               "sample": f"all {cfg.n_kv_heads} KV-head units of each of the {cfg.n_shards} shards, "
+                                         f"{rows} of the {cfg.L_q} query rows per head, scaled by {scale:g}"}
+    return out
 
 
 def main():
@@ -665,14 +781,20 @@ def main():
     per_call = {}
     for name, t in calls.items():
         gbs = g["bytes"][name] / (t["avg_us"] * 1e-6) / 1e9
-        per_call[name] = {"avg_us": round(t["avg_us"], 2), "calls_per_step": t["calls"] // args.steps,
+        per_call[name] = {"avg_us": round(t["avg_us"], 2), "med_us": round(t["med_us"], 2),
+                          "calls_per_step": t["calls"] // args.steps,
                           "bytes": g["bytes"][name], "GB/s": round(gbs, 1), "frac_hbm": round(gbs / HBM_PEAK_GBS, 4)}
     kernel_of = {"scramble_kv": "scramble_rows_kernel<BF16,128,false,0>", "partial_attn": "decode_attn_kernel<BF16,128>"}
     dom = max(kernel_of, key=lambda n: calls[n]["total_ms"])
-    roofline = {"bound": "hbm", "achieved": per_call[dom]["GB/s"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(per_call[dom]["GB/s"] / HBM_PEAK_GBS, 4), "traffic": MEASURED_TRAFFIC_BYTES.get(dom),
-                "kernel": kernel_of[dom], "call": dom, "avg_us": per_call[dom]["avg_us"],
-                "bytes_per_launch": g["bytes"][dom]}
+    def hbm_roofline(name):
+        return {"bound": "hbm", "achieved": per_call[name]["GB/s"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(per_call[name]["GB/s"] / HBM_PEAK_GBS, 4), "traffic": MEASURED_TRAFFIC_BYTES.get(name),
+                "traffic_source": f"{TRAFFIC_PROFILE} (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of this command, scaled "
+                                  "by a 1 GiB copy; not re-read in this run)",
+                "kernel": kernel_of[name], "call": name, "avg_us": per_call[name]["avg_us"],
+                "med_us": per_call[name]["med_us"], "bytes_per_launch": g["bytes"][name]}
+    # the kernel with the largest share of the step's time
+    roofline = hbm_roofline(dom)
     # the spec kernel on its own: K'/V' streaming of partial_attn (+ split merge) over the 4 shards
     attn = per_call["partial_attn"]
 
@@ -685,6 +807,9 @@ def main():
                                "step = scramble_q + 4x(scramble_kv + partial_attn) + lse_merge + unscramble",
                    "step_bytes": g["step_bytes"]},
         "roofline": roofline,
+        # every kernel a target is stated for: the decode attention kernel (HBM) here, the prefill one (MFMA) is added
+        # by the prefill leg below
+        "rooflines": {"scramble_kv": hbm_roofline("scramble_kv"), "decode_partial_attn": hbm_roofline("partial_attn")},
         "decode_partial_attn": {"GB/s": attn["GB/s"], "frac_hbm": attn["frac_hbm"], "avg_us": attn["avg_us"]},
         "calls": per_call,
     }
@@ -700,7 +825,7 @@ def main():
                                     "synchronisations (outputs checked equal to the eager ones bit for bit); "
                                     "'eager' = the same K steps launched call by call from Python")
     line["frac_hbm"] = round(line["value"] / HBM_PEAK_GBS, 4)
-    all_legs = ("shards", "codec", "structured", "rerank", "local_attn", "request", "mixed70b", "prefill",
+    all_legs = ("achievable", "shards", "codec", "structured", "rerank", "local_attn", "request", "mixed70b", "prefill",
                 "long_decode")
     want = set(all_legs) if args.legs == "all" else {x for x in args.legs.split(",") if x and x != "none"}
     unknown = want - set(all_legs)
@@ -722,6 +847,7 @@ def main():
             line[name] = {"error": f"{type(e).__name__}: {e}"}
             print(f"bench.py: leg {name} failed: {e}", file=sys.stderr)
 
+    leg("achievable", lambda: achievable_leg(torch, dev))
     leg("shards", lambda: shards_leg(torch, fb, g, args.steps, args.warmup))
     leg("codec", lambda: codec_leg(torch, fb, g, args.steps, args.warmup))
     leg("structured", lambda: structured_leg(torch, W, fb, g, dev, args.steps, args.warmup))
@@ -729,13 +855,21 @@ def main():
     leg("local_attn", lambda: local_attn_leg(torch, W, fb, dev, half, args.warmup))
     leg("request", lambda: request_leg(torch, W, fb, dev, half, args.warmup))
     leg("mixed70b", lambda: mixed_leg(torch, W, fb, dev, half, args.warmup))
-    leg("prefill", lambda: prefill_leg(torch, W, fb, dev, half, args.warmup))
+    kept = {}
+    leg("prefill", lambda: prefill_leg(torch, W, fb, dev, half, args.warmup, keep=None if args.no_cpu else kept))
+    if isinstance(line.get("prefill"), dict) and "roofline" in line["prefill"]:
+        line["rooflines"]["prefill_partial_attn"] = line["prefill"]["roofline"]
     if not args.no_cpu:
         line["cpu_baseline"] = cpu_leg(torch, W, g, args.cpu_shards)
+        try:
+            line["cpu_baseline"]["other_configs"] = cpu_other_configs(torch, W, kept)
+        except Exception as e:  # noqa: BLE001 - the headline baseline above is already measured
+            line["cpu_baseline"]["other_configs"] = {"error": f"{type(e).__name__}: {e}"}
+    kept.clear()
     if "long_decode" in want:   # last: it takes 64 GiB of device memory
         del g
         torch.cuda.empty_cache()
-        leg("long_decode", lambda: long_decode_leg(torch, W, fb, dev, 5, args.warmup))
+        leg("long_decode", lambda: long_decode_leg(torch, W, fb, dev, half, args.warmup))
     print(json.dumps(line))
 
 

@@ -77,6 +77,19 @@ def build_library(force: bool = True, verbose: bool = False, extra_flags=(), job
     return LIB_PATH
 
 
+PROBES_SRC = os.path.join(CSRC, "probes", "rate_probes.hip")
+PROBES_LIB = os.path.join(_HERE, "libfedrag_probes.so")
+
+
+def build_probes(force: bool = True, verbose: bool = False) -> str:
+    """The reference-rate kernels of bench.py (plain copy, plain read, bare MFMA loop) as a library of their own."""
+    if not force and os.path.exists(PROBES_LIB) and os.path.getmtime(PROBES_LIB) >= os.path.getmtime(PROBES_SRC):
+        return PROBES_LIB
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    _run([hipcc] + HIPCC_FLAGS + ["-shared", "-o", PROBES_LIB, PROBES_SRC], verbose)
+    return PROBES_LIB
+
+
 SAN_DIR = os.path.join(OBJ_DIR, "san")
 SAN_FLAGS = ["-O1", "-g", "-fno-omit-frame-pointer",
              # host code only: each -fsanitize= goes directly behind an -Xarch_host (the device side has no sanitizer)
@@ -113,3 +126,4 @@ def build_host_check(c_driver: str, force: bool = False, verbose: bool = False, 
 if __name__ == "__main__":
     import sys
     print(build_library(force="--incremental" not in sys.argv, verbose=True))
+    print(build_probes(force="--incremental" not in sys.argv, verbose=True))

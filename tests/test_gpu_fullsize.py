@@ -110,7 +110,9 @@ def test_llama8b_decode_shard_full_size(oracle):
 
 
 def test_rag_prefill_full_size(oracle):
-    run_fullsize(oracle, W.CONFIGS["rag_prefill"], n_units=2, q_rows_per_head=96, heads_per_unit=2)
+    # 4 of the 8 KV heads, 2 query heads each, 256 rows per head: the printed worst error is a maximum over
+    # 8 heads x 256 rows x 128 channels
+    run_fullsize(oracle, W.CONFIGS["rag_prefill"], n_units=4, q_rows_per_head=256, heads_per_unit=2)
 
 
 def test_long_decode_shard_full_size(oracle):
@@ -123,6 +125,108 @@ def test_mixed70b_decode_shard_full_size(oracle):
 
 def test_mixed70b_prefill_shard_full_size(oracle):
     run_fullsize(oracle, W.CONFIGS["mixed70b_prefill"], n_units=1, q_rows_per_head=64, heads_per_unit=2)
+
+
+def run_shards_fullsize(oracle, cfg, n_units, q_rows_per_head=None, heads_per_unit=None):
+    """fedrag_partial_attn_shards over ALL shards of a configuration at full size, in the launch configuration
+    bench.py times (Section 4.1: per-shard computation and aggregation = attention over all keys).  Every shard is
+    drawn by the seeded generator with outlier channels and scrambled on the GPU; for a seeded sample of
+    (sequence, KV head) units the device K', V' of every shard and the unit's Q' are replaced by the oracle's own
+    rounded Enc, so that both sides consume identical bits that never came from the HIP path.  The sampled rows
+    are recomputed by the oracle shard by shard, aggregated by the oracle, and also computed over the concatenated keys."""
+    dt = W.torch_dtype(cfg.dtype)
+    G, S, d = cfg.group, cfg.n_shards, cfg.d_head
+    keys = W.make_keys(cfg.n_kv_heads, d, cfg.L_q, cfg.L_kv, S, seed=cfg.seed, dtype=dt)
+    phi = {k: getattr(keys, k).to(DEV) for k in ("phi_q", "phi_k", "phi_v")}
+    rng = np.random.default_rng(cfg.seed + 31)
+    all_units = [(b, g) for b in range(cfg.batch) for g in range(cfg.n_kv_heads)]
+    units = [all_units[i] for i in rng.choice(len(all_units), size=min(n_units, len(all_units)), replace=False)]
+    heads = {}
+    for (b, g) in units:
+        hs = list(range(g * G, (g + 1) * G))
+        if heads_per_unit is not None and heads_per_unit < G:
+            hs = sorted(hs[i] for i in rng.choice(G, size=heads_per_unit, replace=False))
+        heads[(b, g)] = hs
+    gs = [g for (_, g) in units]
+
+    Q = W.activations(cfg.batch, cfg.n_q_heads, cfg.L_q, d, seed=cfg.seed, tensor_id=W.TID_Q, outliers=cfg.outliers,
+                      dtype=dt, device=DEV)
+    Qs = fb.fedrag_scramble_q(Q, phi["phi_q"], None if keys.perm_q is None else keys.perm_q.to(DEV))
+    Qo = {}
+    for (b, g) in units:
+        hs = heads[(b, g)]
+        q = oracle.scramble(Q[b:b + 1, hs].cpu(), keys.phi_q[g:g + 1].repeat(len(hs), 1, 1), keys.perm_q)
+        Qo[(b, g)] = rounded(q, dt)                      # [1, len(hs), Lq, d]
+        Qs[b, hs] = Qo[(b, g)][0].to(DEV)
+    del Q
+    Ks, Vs, Ko, Vo = [], [], [], []
+    for s_ in range(S):
+        K = W.activations(cfg.batch, cfg.n_kv_heads, cfg.L_kv, d, seed=cfg.seed, tensor_id=W.TID_K + s_,
+                          outliers=cfg.outliers, outlier_id=W.TID_K, dtype=dt, device=DEV)
+        V = W.activations(cfg.batch, cfg.n_kv_heads, cfg.L_kv, d, seed=cfg.seed, tensor_id=W.TID_V + s_,
+                          outliers=cfg.outliers, outlier_id=W.TID_V, dtype=dt, device=DEV)
+        perm = keys.perm_kv[s_]
+        Kd, Vd = fb.fedrag_scramble_kv(K, V, phi["phi_k"], phi["phi_v"], perm.to(DEV), n_q_heads=cfg.n_q_heads)
+        # the sampled units as the "heads" of one oracle call (it runs its units in parallel)
+        Kp = torch.stack([K[b, g] for (b, g) in units])[None].cpu()
+        Vp = torch.stack([V[b, g] for (b, g) in units])[None].cpu()
+        del K, V
+        ko = rounded(oracle.scramble(Kp, keys.phi_k[gs], perm), dt)
+        vo = rounded(oracle.scramble(Vp, keys.phi_v[gs], perm), dt)
+        mism = 0.0
+        for i, (b, g) in enumerate(units):
+            mism = max(mism, float((Kd[b, g].cpu() != ko[0, i]).float().mean()), float((Vd[b, g].cpu() != vo[0, i]).float().mean()))
+            Kd[b, g] = ko[0, i].to(DEV)
+            Vd[b, g] = vo[0, i].to(DEV)
+        assert mism <= 0.03, f"shard {s_}: Enc differs from round(oracle) on {mism:.4f} of a unit's elements"
+        Ks.append(Kd); Vs.append(Vd); Ko.append(ko); Vo.append(vo)
+
+    O, lse = fb.fedrag_partial_attn_shards(Qs, Ks, Vs)
+    torch.cuda.synchronize()
+    assert torch.isfinite(O).all() and torch.isfinite(lse).all()
+    worst_o = worst_l = worst_cat = 0.0
+    for i, (b, g) in enumerate(units):
+        for j, h in enumerate(heads[(b, g)]):
+            rows = np.arange(cfg.L_q)
+            if q_rows_per_head is not None and cfg.L_q > q_rows_per_head:
+                rows = np.sort(rng.choice(cfg.L_q, size=q_rows_per_head, replace=False))
+            q = Qo[(b, g)][:, j:j + 1][:, :, rows]
+            parts = [oracle.partial_attn(q, Ko[s_][:, i:i + 1], Vo[s_][:, i:i + 1]) for s_ in range(S)]
+            Or, lr = oracle.lse_merge(np.stack([p[0] for p in parts]), np.stack([p[1] for p in parts]))
+            got_O, got_l = O[b:b + 1, h:h + 1][:, :, rows], lse[b:b + 1, h:h + 1][:, :, rows]
+            eo, el = PT.check_attn(got_O, got_l, Or, lr, dt, f"{cfg.name} all shards, unit {(b, g)} head {h}")
+            worst_o, worst_l = max(worst_o, eo), max(worst_l, el)
+            Oc, lc = oracle.partial_attn(q, torch.cat([k[:, i:i + 1] for k in Ko], 2), torch.cat([v[:, i:i + 1] for v in Vo], 2))
+            ec, _ = PT.check_attn(got_O, got_l, Oc, lc, dt, f"{cfg.name} vs concatenated keys, unit {(b, g)} head {h}")
+            worst_cat = max(worst_cat, ec)
+    print(f"{cfg.name}, {S} shards in one call, full size: units {units}: worst O err {worst_o:.3e} (vs concatenated keys "
+          f"{worst_cat:.3e}), worst lse err {worst_l:.3e}")
+
+
+def test_all_shards_helper_on_a_small_configuration(oracle):
+    """The same procedure at a size where every unit can be sampled (decode and prefill shapes, ragged shards)."""
+    run_shards_fullsize(oracle, W.CONFIGS["llama8b_decode"].scaled(batch=2, n_shards=3, L_kv=333), n_units=16)
+    run_shards_fullsize(oracle, W.CONFIGS["mixed70b_prefill"].scaled(L_q=300, n_shards=2, L_kv=200), n_units=8,
+                        q_rows_per_head=40, heads_per_unit=3)
+
+
+def test_llama8b_decode_all_shards_with_outliers_full_size(oracle):
+    run_shards_fullsize(oracle, W.CONFIGS["llama8b_decode"], n_units=4)
+
+
+def test_long_decode_all_shards_full_size(oracle):
+    """8 shards x 32768 keys, 64 sequences: 64 GiB of K', V' resident, the launch bench.py's long_decode leg times."""
+    run_shards_fullsize(oracle, W.CONFIGS["long_decode"], n_units=4)
+
+
+def test_mixed70b_decode_all_shards_full_size(oracle):
+    run_shards_fullsize(oracle, W.CONFIGS["mixed70b_decode"], n_units=4)
+
+
+def test_mixed70b_prefill_all_shards_full_size(oracle):
+    """The 4096-token chunk against 8 shards x 8192 keys, 64 query heads: enough query tiles to cover the chip, so the
+    call launches shard by shard and aggregates the 8 partials."""
+    run_shards_fullsize(oracle, W.CONFIGS["mixed70b_prefill"], n_units=2, q_rows_per_head=128, heads_per_unit=2)
 
 
 def test_structured_scramble_kv_full_size(oracle):
