@@ -313,17 +313,32 @@ fedrag_status fedrag_scramble_kv_structured_quantized(const fedrag_shape* shape,
  * the codes and dequantises them on the fly, so only d * bits / 8 + 8 bytes per key row are read instead of 2 d.
  * Every element is reconstructed exactly as fedrag_dequantize_rows would (fp32 fma, one narrowing to the storage
  * type), so the call works on the same values as fedrag_partial_attn(fedrag_dequantize_rows(...)); the two results
- * differ only by the order in which the channels of <q, k> are summed in fp32 (a few 1e-6).
- * Qs : [B,Hq,L_q,d] storage type (16-bit);  K_codes, V_codes : uint8 [B,Hkv,L_kv,d*bits/8];
- * K_params, V_params : fp32 [B,Hkv,L_kv,2] (8-byte aligned).  bits in {8, 4}.
- * Only the decode shape is served: d_head = 128 and (n_q_heads / n_kv_heads) * L_q <= 16; anything else returns
- * FEDRAG_ERR_UNSUPPORTED (dequantise, then call fedrag_partial_attn).  Workspace rule as fedrag_partial_attn.
+ * differ only by the order in which fp32 sums are formed (a few 1e-6 for decode shapes, where probabilities enter the
+ * second product as two storage-type terms; within the 16-bit bounds of fedrag_partial_attn otherwise).
+ * Qs : [B,Hq,L_q,d] storage type (16-bit; FEDRAG_F32 is FEDRAG_ERR_UNSUPPORTED);  K_codes, V_codes : uint8
+ * [B,Hkv,L_kv,d*bits/8];  K_params, V_params : fp32 [B,Hkv,L_kv,2] (8-byte aligned).  bits in {8, 4}.
+ * Any L_q: decode shapes ((n_q_heads / n_kv_heads) * L_q <= 16, d = 128) stream the codes; everything else - the
+ * re-ranker's and the prefill shapes of Sections 5.2 and 5.3 - rebuilds each key tile in on-chip memory.
+ * Workspace rule as fedrag_partial_attn.
  */
 fedrag_status fedrag_partial_attn_quantized(const fedrag_shape* shape, int64_t L_q, int64_t L_kv, const void* Qs,
                                             const uint8_t* K_codes, const float* K_params,
                                             const uint8_t* V_codes, const float* V_params, int32_t bits,
                                             float softmax_scale, float* O_part, float* lse,
                                             void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * fedrag_partial_attn_varlen on transport codes: the re-ranker's padded batch of query-document pairs (Section 5.2)
+ * with K', V' travelling at 8 or 4 bits (Section 7.5 recommends 4 bits for the re-ranking phase).  kv_lens, q_lens
+ * as in fedrag_partial_attn_varlen (rows of the code and parameter tensors past kv_lens[b] are never used and may
+ * hold anything); the other arguments as in fedrag_partial_attn_quantized.
+ */
+fedrag_status fedrag_partial_attn_varlen_quantized(const fedrag_shape* shape, int64_t L_q, int64_t L_kv,
+                                                   const void* Qs, const uint8_t* K_codes, const float* K_params,
+                                                   const uint8_t* V_codes, const float* V_params, int32_t bits,
+                                                   const int32_t* kv_lens, const int32_t* q_lens,
+                                                   float softmax_scale, float* O_part, float* lse,
+                                                   void* workspace, size_t workspace_bytes, void* stream);
 
 /* inv_out[perm[j]] = j for j in [0, L): the gather array that undoes `perm`.  Device pointers. */
 fedrag_status fedrag_invert_perm(const int32_t* perm, int64_t L, int32_t* inv_out, void* stream);

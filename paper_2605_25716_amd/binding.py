@@ -26,7 +26,8 @@ EXPORTS = ("fedrag_scramble_kv", "fedrag_scramble_q", "fedrag_partial_attn", "fe
            "fedrag_scramble_kv_structured", "fedrag_scramble_q_structured", "fedrag_unscramble_structured",
            "fedrag_local_attn", "fedrag_unpermute_lse", "fedrag_partial_attn_varlen", "fedrag_quantize_rows",
            "fedrag_dequantize_rows", "fedrag_scramble_kv_quantized", "fedrag_scramble_kv_structured_quantized",
-           "fedrag_partial_attn_quantized", "fedrag_invert_perm", "fedrag_validate_perm", "fedrag_status_string",
+           "fedrag_partial_attn_quantized", "fedrag_partial_attn_varlen_quantized", "fedrag_invert_perm",
+           "fedrag_validate_perm", "fedrag_status_string",
            "fedrag_version")
 
 
@@ -96,6 +97,8 @@ def load() -> ctypes.CDLL:
         lib.fedrag_scramble_kv_structured_quantized.argtypes = [sp, i64, vp, vp, kp, kp, vp, i32, i32, vp, vp, vp, vp, vp]
         lib.fedrag_partial_attn_quantized.argtypes = [sp, i64, i64, vp, vp, vp, vp, vp, i32, ctypes.c_float, f32p, f32p,
                                                       vp, ctypes.c_size_t, vp]
+        lib.fedrag_partial_attn_varlen_quantized.argtypes = [sp, i64, i64, vp, vp, vp, vp, vp, i32, vp, vp,
+                                                             ctypes.c_float, f32p, f32p, vp, ctypes.c_size_t, vp]
         lib.fedrag_invert_perm.argtypes = [vp, i64, vp, vp]
         lib.fedrag_validate_perm.argtypes = [vp, i32, i64, vp, vp, vp]
         lib.fedrag_status_string.argtypes = [ctypes.c_int]
@@ -107,7 +110,8 @@ def load() -> ctypes.CDLL:
                      "fedrag_scramble_q_structured", "fedrag_unscramble_structured", "fedrag_local_attn",
                      "fedrag_unpermute_lse", "fedrag_partial_attn_varlen", "fedrag_quantize_rows",
                      "fedrag_dequantize_rows", "fedrag_scramble_kv_quantized",
-                     "fedrag_scramble_kv_structured_quantized", "fedrag_partial_attn_quantized"):
+                     "fedrag_scramble_kv_structured_quantized", "fedrag_partial_attn_quantized",
+                     "fedrag_partial_attn_varlen_quantized"):
             getattr(lib, name).restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -276,7 +280,7 @@ def fedrag_partial_attn_varlen(Qs, Ks, Vs, kv_lens, softmax_scale: Optional[floa
 
 def fedrag_partial_attn_quantized(Qs, K_codes, K_params, V_codes, V_params, bits: int,
                                   softmax_scale: Optional[float] = None, O_part=None, lse=None, workspace=None):
-    """fedrag_partial_attn reading K', V' as transport-codec codes (decode shapes, d = 128)."""
+    """fedrag_partial_attn reading K', V' as transport-codec codes (any query count; 16-bit storage)."""
     B, Hq, Lq, d = Qs.shape
     Hkv, L = K_codes.shape[1], K_codes.shape[2]
     shape = make_shape(B, Hq, Hkv, d, Qs.dtype)
@@ -294,6 +298,33 @@ def fedrag_partial_attn_quantized(Qs, K_codes, K_params, V_codes, V_params, bits
                                               _ptr(V_params) if nz else None, bits, ctypes.c_float(softmax_scale),
                                               _ptr(O_part), _ptr(lse), _ptr(workspace), ws_bytes, _stream())
     _check(st, "fedrag_partial_attn_quantized")
+    return O_part, lse
+
+
+def fedrag_partial_attn_varlen_quantized(Qs, K_codes, K_params, V_codes, V_params, bits: int, kv_lens,
+                                         softmax_scale: Optional[float] = None, O_part=None, lse=None, workspace=None,
+                                         q_lens=None):
+    """fedrag_partial_attn_varlen reading K', V' as transport-codec codes: sequence b attends to its first kv_lens[b]
+    keys; q_lens (optional) gives the real query rows per sequence."""
+    B, Hq, Lq, d = Qs.shape
+    Hkv, L = K_codes.shape[1], K_codes.shape[2]
+    if kv_lens.dtype != torch.int32 or kv_lens.shape != (B,):
+        raise ValueError("kv_lens: int32 [B]")
+    shape = make_shape(B, Hq, Hkv, d, Qs.dtype)
+    if softmax_scale is None:
+        softmax_scale = float(d) ** -0.5
+    O_part = torch.empty((B, Hq, Lq, d), dtype=torch.float32, device=Qs.device) if O_part is None else O_part
+    lse = torch.empty((B, Hq, Lq), dtype=torch.float32, device=Qs.device) if lse is None else lse
+    need = int(load().fedrag_partial_attn_workspace_bytes(ctypes.byref(shape), Lq, L))
+    if workspace is None and need > 0:
+        workspace = torch.empty(need, dtype=torch.uint8, device=Qs.device)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    nz = L > 0
+    st = load().fedrag_partial_attn_varlen_quantized(
+        ctypes.byref(shape), Lq, L, _ptr(Qs), _ptr(K_codes) if nz else None, _ptr(K_params) if nz else None,
+        _ptr(V_codes) if nz else None, _ptr(V_params) if nz else None, bits, _ptr(kv_lens), _ptr(q_lens),
+        ctypes.c_float(softmax_scale), _ptr(O_part), _ptr(lse), _ptr(workspace), ws_bytes, _stream())
+    _check(st, "fedrag_partial_attn_varlen_quantized")
     return O_part, lse
 
 

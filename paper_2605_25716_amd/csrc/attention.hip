@@ -305,10 +305,11 @@ hipError_t launch_partial_attn(const AttnProblem& p_in, hipStream_t stream) {
         return decode ? launch_decode_attn(p, stream) : launch_prefill_attn(p, stream);
     }
     if (p.Lkv == 0) return launch_fill_empty(p.O, p.lse, rows, p.D, stream);
-    if (p.quant_bits != 0) {  // only the decode kernel reads the codec's codes
-        if (p.dtype == FEDRAG_F32 || p.causal || p.kv_lens || !use_decode_kernel(p.Hq, p.Hkv, p.Lq))
-            return hipErrorInvalidValue;
-        return launch_decode_attn(p, stream);
+    if (p.quant_bits != 0) {  // K', V' as transport codes: 16-bit storage, no mask
+        if (p.dtype == FEDRAG_F32 || p.causal) return hipErrorInvalidValue;
+        // the streaming kernel's code path is laid out for d = 128; everything else takes the tiled kernel
+        return (use_decode_kernel(p.Hq, p.Hkv, p.Lq) && p.D == 128) ? launch_decode_attn(p, stream)
+                                                                    : launch_prefill_attn(p, stream);
     }
     if (p.dtype == FEDRAG_F32) return p.D == 128 ? launch_attn_f32<128>(p, stream) : launch_attn_f32<64>(p, stream);
     if (p.dtype != FEDRAG_BF16 && p.dtype != FEDRAG_F16) return hipErrorInvalidValue;

@@ -12,7 +12,11 @@
 //     tile already sits in the lane layout the second product wants for P^T: probabilities never cross lanes.
 //     K' operands are 16-byte LDS reads; V'^T operands come from the row-major V' tile through the transposing LDS
 //     read (ds_read_b64_tr_b16), so V' is never transposed in memory or in registers;
-//   * workgroups that share a KV head are placed on the same XCD (shared L2).
+//   * workgroups that share a KV head are placed on the same XCD (shared L2);
+//   * QB = 8 or 4: K', V' arrive as the transport codec's codes (Section 7.5).  The LDS-direct loads are replaced by
+//     ordinary loads of the codes and of the rows' (scale, lo) one iteration ahead; each thread rebuilds its 8-element
+//     chunk exactly as the dequantise call would (fp32 fma, one narrowing) and writes it to the same swizzled LDS slot,
+//     so everything downstream is unchanged and consumes the same values as dequantise-then-attend.
 #include <type_traits>
 
 #include "fedrag_device.h"
@@ -42,9 +46,12 @@ __device__ __forceinline__ u32x2_t lds_read_tr16(const char* p) {
 // storage type (relative error 2^-9 in bf16) would move an output by more than the 16-bit output tolerance.  The
 // CAUSAL instantiation therefore feeds the second product P = P_hi + P_lo, two storage-type terms (about 16
 // significant bits), at the price of twice the MFMAs of that product.
-template <class T, int D, bool CAUSAL>
+template <class T, int D, bool CAUSAL, int QB>
 __global__ __launch_bounds__(kPreThreads, 1) void prefill_attn_kernel(const typename T::elem* __restrict__ Q,
-                                                                      const KeyRuns runs, int Hq, int Hkv, int64_t Lq,
+                                                                      const KeyRuns runs,
+                                                                      const float* __restrict__ Kprm,
+                                                                      const float* __restrict__ Vprm, int Hq, int Hkv,
+                                                                      int64_t Lq,
                                                                       const int32_t* __restrict__ kv_lens,
                                                                       const int32_t* __restrict__ q_lens, int q_tiles,
                                                                       int n_units, float scale_log2,
@@ -56,7 +63,10 @@ __global__ __launch_bounds__(kPreThreads, 1) void prefill_attn_kernel(const type
     constexpr int KS = D / 16;              // contraction steps of S^T
     constexpr int MT = D / 32;              // 32-row tiles of O^T
     constexpr int CH = D / 8;               // 16-byte chunks per row
-    constexpr int LPT = (kPreK * CH) / kPreThreads;  // LDS-direct loads per thread per tile
+    constexpr int LPT = (kPreK * CH) / kPreThreads;  // LDS-direct loads (QB: 8-element chunks) per thread per tile
+    static_assert(QB == 0 || QB == 8 || QB == 4, "16-bit values, or 8- / 4-bit codes");
+    static_assert(QB == 0 || !CAUSAL, "codes are what travels to the Compute Node; the Inquirer's own K, V are plain");
+    constexpr int CROWB = QB ? D * QB / 8 : ROWB;  // bytes per row of K' / V' as stored (values, or codes)
 
     // One array per tile slot: distinct objects let the compiler see that the LDS-direct load filling one slot
     // does not alias the LDS reads of another, so it does not make those reads wait for the load.
@@ -107,8 +117,10 @@ __global__ __launch_bounds__(kPreThreads, 1) void prefill_attn_kernel(const type
     const int lh = lane / 32;
 
     const elem* Qh = Q + ((int64_t)b * Hq + h) * Lq * D;
-    const char* Kg = (const char*)(K + ((int64_t)b * Hkv + g) * L_stride * D);
-    const char* Vg = (const char*)(V + ((int64_t)b * Hkv + g) * L_stride * D);
+    const char* Kg = (const char*)K + ((int64_t)b * Hkv + g) * L_stride * CROWB;
+    const char* Vg = (const char*)V + ((int64_t)b * Hkv + g) * L_stride * CROWB;
+    const float* Kpg = QB ? Kprm + ((int64_t)b * Hkv + g) * L_stride * 2 : nullptr;  // (scale, lo) per key row
+    const float* Vpg = QB ? Vprm + ((int64_t)b * Hkv + g) * L_stride * 2 : nullptr;
     // keys of this sequence: all L_stride rows, or the first kv_lens[b] of them (padded batch of unequal sequences)
     int64_t L = L_stride;
     if (kv_lens) {
@@ -129,8 +141,12 @@ __global__ __launch_bounds__(kPreThreads, 1) void prefill_attn_kernel(const type
         const int64_t k_begin = (int64_t)split * keys_per_run;
         const int64_t k_end = k_begin + keys_per_run < L ? k_begin + keys_per_run : L;
         L = k_end > k_begin ? k_end - k_begin : 0;
-        Kg += k_begin * ROWB;
-        Vg += k_begin * ROWB;
+        Kg += k_begin * CROWB;
+        Vg += k_begin * CROWB;
+        if (QB) {
+            Kpg += k_begin * 2;
+            Vpg += k_begin * 2;
+        }
     }
 
     const int64_t q_row = (int64_t)qt * kPreQTile + wave * kPreQ + li;  // this lane's query row
@@ -171,6 +187,55 @@ __global__ __launch_bounds__(kPreThreads, 1) void prefill_attn_kernel(const type
             char* lp = slot_base + (j * kPreWaves + wave) * (RPW * ROWB);  // wave-uniform LDS base
             __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (void __attribute__((address_space(3)))*)lp, 16,
                                                      is_k ? ld_voff_k : ld_voff_v, j * (kPreWaves * RPW * ROWB), 0, 0);
+        }
+    };
+
+    // ---- QB: codes -> registers one iteration ahead, then -> LDS.  Chunk j of a thread is row (j * kPreThreads + tid)
+    // / CH of the tile, 8 channels from 8 (tid % CH); reads past the end of the shard return zeros (code 0, scale 0,
+    // lo 0: the row dequantises to zeros, as rows past the end arrive in the 16-bit path).
+    struct CodeChunk {
+        uint32_t c[QB == 8 ? 2 : 1];
+        u32x2_t prm;
+    };
+    CodeChunk kst[QB ? LPT : 1], vst[QB ? LPT : 1];
+    const int cq_row = tid / CH, cq_c = tid % CH;
+    auto fetch_codes = [&](const char* G_, const float* Pg_, int tile, CodeChunk (&st)[QB ? LPT : 1]) {
+        const int64_t row0 = (int64_t)tile * kPreK;
+        const int64_t left_rows = L - row0 > 0 ? L - row0 : 0;
+        const int64_t lc = left_rows * CROWB, lp = left_rows * 8;
+        const __amdgpu_buffer_rsrc_t rc = __builtin_amdgcn_make_buffer_rsrc(
+            (void*)(G_ + row0 * CROWB), 0, (int)(lc < 0x7fffffff ? lc : 0x7fffffff), 0x00020000);
+        const __amdgpu_buffer_rsrc_t rp = __builtin_amdgcn_make_buffer_rsrc(
+            (void*)(Pg_ + row0 * 2), 0, (int)(lp < 0x7fffffff ? lp : 0x7fffffff), 0x00020000);
+#pragma unroll
+        for (int j = 0; j < LPT; ++j) {
+            const int r = j * (kPreThreads / CH) + cq_row;
+            if constexpr (QB == 8) {
+                const u32x2_t w = __builtin_amdgcn_raw_buffer_load_b64(rc, r * CROWB + cq_c * 8, 0, 0);
+                st[j].c[0] = w[0];
+                st[j].c[1] = w[1];
+            } else {
+                st[j].c[0] = __builtin_amdgcn_raw_buffer_load_b32(rc, r * CROWB + cq_c * 4, 0, 0);
+            }
+            st[j].prm = __builtin_amdgcn_raw_buffer_load_b64(rp, r * 8, 0, 0);
+        }
+    };
+    auto store_codes = [&](char* slot_base, const CodeChunk (&st)[QB ? LPT : 1], bool is_k) {
+#pragma unroll
+        for (int j = 0; j < LPT; ++j) {
+            const int r = j * (kPreThreads / CH) + cq_row;
+            const uint32_t sb = st[j].prm[0], lb = st[j].prm[1];
+            const float scale = __builtin_bit_cast(float, sb), lo = __builtin_bit_cast(float, lb);
+            vec8 out;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const uint32_t code = QB == 8 ? (st[j].c[e / 4] >> (8 * (e % 4))) & 255u : (st[j].c[0] >> (4 * e)) & 15u;
+                float x = __builtin_fmaf((float)code, scale, lo);
+                pin_here(x);  // the dequantised value is the fp32 result narrowed afterwards: two roundings, not one
+                out[e] = T::from_float(x);
+            }
+            const int swz = is_k ? r % CH : (4 * (r % 4)) % CH;
+            *(vec8*)(slot_base + r * ROWB + ((cq_c ^ swz) << 4)) = out;
         }
     };
 
@@ -236,8 +301,13 @@ __global__ __launch_bounds__(kPreThreads, 1) void prefill_attn_kernel(const type
         constexpr int q = 1 - p;                 // (t - 1) & 1 == (t + 1) & 1
         constexpr int NM = 4 * MT;
         static_assert(NM == 16 || NM == 8, "slice plans assume d = 128 or 64");
-        if (ldK) load_tile(Kg, q ? ks1 : ks0, t + 1, true);    // K'(t+1) -> slot (t+1) & 1 (last read by A(t-1))
-        if (doAB) load_tile(Vg, p ? vs1 : vs0, t, false);      // V'(t)   -> slot t & 1     (last read by C(t-2))
+        if constexpr (QB == 0) {
+            if (ldK) load_tile(Kg, q ? ks1 : ks0, t + 1, true);    // K'(t+1) -> slot (t+1) & 1 (last read by A(t-1))
+            if (doAB) load_tile(Vg, p ? vs1 : vs0, t, false);      // V'(t)   -> slot t & 1     (last read by C(t-2))
+        } else {  // the codes of the same two tiles into registers; they reach their (free) slots between the phases
+            if (ldK) fetch_codes(Kg, Kpg, t + 1, kst);
+            if (doAB) fetch_codes(Vg, Vpg, t, vst);
+        }
         const bool steady = doC && doAB && !may_mask;
 
         // --- A(t) and B2(t-1).  Lane gets query li and, per 32-key half, keys 8 (r / 4) + 4 lh + r % 4, r = 0..15.
@@ -291,6 +361,10 @@ __global__ __launch_bounds__(kPreThreads, 1) void prefill_attn_kernel(const type
             }
         }
         __builtin_amdgcn_sched_barrier(0);
+        if constexpr (QB != 0) {
+            if (ldK) store_codes(q ? ks1 : ks0, kst, true);
+            __builtin_amdgcn_sched_barrier(0);
+        }
         const char* vt = q ? vs1 : vs0;
         if (doC) {
             if (__builtin_amdgcn_ballot_w64(alph[q] != 1.0f) != 0) {  // wave-uniform: skip when no maximum moved
@@ -381,6 +455,9 @@ __global__ __launch_bounds__(kPreThreads, 1) void prefill_attn_kernel(const type
                 m_run = m_new;
             }
         }
+        if constexpr (QB != 0) {
+            if (doAB) store_codes(p ? vs1 : vs0, vst, false);
+        }
         // keep this iteration's results above the barrier that follows (they are consumed in the next iteration)
 #pragma unroll
         for (int kk = 0; kk < 2; ++kk) {
@@ -401,7 +478,12 @@ __global__ __launch_bounds__(kPreThreads, 1) void prefill_attn_kernel(const type
     std::integral_constant<int, 1> odd;
 
     // prologue: K'(0)
-    load_tile(Kg, ks0, 0, true);
+    if constexpr (QB == 0) {
+        load_tile(Kg, ks0, 0, true);
+    } else {
+        fetch_codes(Kg, Kpg, 0, kst);
+        store_codes(ks0, kst, true);
+    }
     alph[0] = alph[1] = 1.0f;
     __syncthreads();
 
@@ -439,7 +521,7 @@ __global__ __launch_bounds__(kPreThreads, 1) void prefill_attn_kernel(const type
     }
 }
 
-template <class T, int D, bool CAUSAL>
+template <class T, int D, bool CAUSAL, int QB = 0>
 static hipError_t launch_prefill_t(const AttnProblem& p, hipStream_t stream) {
     typedef typename T::elem elem;
     const float scale_log2 = p.scale * kLog2e;
@@ -473,9 +555,10 @@ static hipError_t launch_prefill_t(const AttnProblem& p, hipStream_t stream) {
     const int64_t per_unit = (int64_t)(Hq_k / p.Hkv) * q_tiles * splits;
     const int64_t grid = (int64_t)8 * ((n_units + 7) / 8) * per_unit;
     if (!grid_fits(grid)) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((prefill_attn_kernel<T, D, CAUSAL>), dim3((unsigned)grid), dim3(kPreThreads), 0, stream,
-                       (const elem*)p.Q, runs, Hq_k, p.Hkv, Lq_k, p.kv_lens, p.q_lens, q_tiles, n_units, scale_log2,
-                       Odst, Ldst);
+    if (QB != 0 && (p.n_shards > 1 || !p.K_params || !p.V_params)) return hipErrorInvalidValue;
+    hipLaunchKernelGGL((prefill_attn_kernel<T, D, CAUSAL, QB>), dim3((unsigned)grid), dim3(kPreThreads), 0, stream,
+                       (const elem*)p.Q, runs, p.K_params, p.V_params, Hq_k, p.Hkv, Lq_k, p.kv_lens, p.q_lens,
+                       q_tiles, n_units, scale_log2, Odst, Ldst);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess || splits == 1) return e;
     return launch_lse_merge(Odst, Ldst, splits, rows, D, p.O, p.lse, stream);
@@ -483,6 +566,12 @@ static hipError_t launch_prefill_t(const AttnProblem& p, hipStream_t stream) {
 
 template <class T>
 static hipError_t launch_prefill_d(const AttnProblem& p, hipStream_t stream) {
+    if (p.quant_bits != 0) {  // K', V' as transport codes (never with the mask: the Inquirer's own K, V are plain)
+        if (p.causal || (p.quant_bits != 8 && p.quant_bits != 4)) return hipErrorInvalidValue;
+        if (p.quant_bits == 8)
+            return p.D == 128 ? launch_prefill_t<T, 128, false, 8>(p, stream) : launch_prefill_t<T, 64, false, 8>(p, stream);
+        return p.D == 128 ? launch_prefill_t<T, 128, false, 4>(p, stream) : launch_prefill_t<T, 64, false, 4>(p, stream);
+    }
     if (p.causal)
         return p.D == 128 ? launch_prefill_t<T, 128, true>(p, stream) : launch_prefill_t<T, 64, true>(p, stream);
     return p.D == 128 ? launch_prefill_t<T, 128, false>(p, stream) : launch_prefill_t<T, 64, false>(p, stream);

@@ -281,18 +281,19 @@ fedrag_status fedrag_partial_attn_varlen(const fedrag_shape* shape, int64_t L_q,
     return dev(launch_partial_attn(p, (hipStream_t)stream));
 }
 
-fedrag_status fedrag_partial_attn_quantized(const fedrag_shape* shape, int64_t L_q, int64_t L_kv, const void* Qs,
-                                            const uint8_t* K_codes, const float* K_params, const uint8_t* V_codes,
-                                            const float* V_params, int32_t bits, float softmax_scale, float* O_part,
-                                            float* lse, void* workspace, size_t workspace_bytes, void* stream) {
+// fedrag_partial_attn / fedrag_partial_attn_varlen on transport codes; kv_lens == NULL and !lens_required: every key.
+static fedrag_status attn_on_codes(const fedrag_shape* shape, int64_t L_q, int64_t L_kv, const void* Qs,
+                                   const uint8_t* K_codes, const float* K_params, const uint8_t* V_codes,
+                                   const float* V_params, int32_t bits, const int32_t* kv_lens, const int32_t* q_lens,
+                                   bool lens_required, float softmax_scale, float* O_part, float* lse, void* workspace,
+                                   size_t workspace_bytes, void* stream) {
     fedrag_status st = check_shape(shape, true);
     if (st != FEDRAG_OK) return st;
     if (bits != 8 && bits != 4) return FEDRAG_ERR_UNSUPPORTED;
-    if (shape->dtype == FEDRAG_F32 || shape->d_head != 128) return FEDRAG_ERR_UNSUPPORTED;
+    if (shape->dtype == FEDRAG_F32) return FEDRAG_ERR_UNSUPPORTED;  // the codec travels with 16-bit storage
     if (L_q < 0 || L_kv < 0 || L_q > INT32_MAX || L_kv > INT32_MAX) return FEDRAG_ERR_SHAPE;
-    if (!attn_uses_decode_kernel(shape->n_q_heads, shape->n_kv_heads, L_q)) return FEDRAG_ERR_UNSUPPORTED;
     if (L_q == 0 || shape->batch == 0) return FEDRAG_OK;  // no rows: nothing to do, tensor pointers may be NULL
-    if (!Qs || !O_part || !lse) return FEDRAG_ERR_NULL;
+    if (!Qs || !O_part || !lse || (lens_required && !kv_lens)) return FEDRAG_ERR_NULL;
     if (L_kv > 0 && (!K_codes || !K_params || !V_codes || !V_params)) return FEDRAG_ERR_NULL;
     int64_t nq, nk;
     if (!tensor_elems(shape->batch, shape->n_q_heads, L_q, shape->d_head, &nq) ||
@@ -301,7 +302,8 @@ fedrag_status fedrag_partial_attn_quantized(const fedrag_shape* shape, int64_t L
     if (!(softmax_scale > 0.0f) || softmax_scale - softmax_scale != 0.0f) return FEDRAG_ERR_SHAPE;  // finite, > 0
     if (!aligned16(Qs) || !aligned16(K_codes) || !aligned16(V_codes) || !aligned16(O_part) ||
         (reinterpret_cast<uintptr_t>(K_params) & 7u) || (reinterpret_cast<uintptr_t>(V_params) & 7u) ||
-        (reinterpret_cast<uintptr_t>(lse) & 3u) || !aligned16(workspace))
+        (reinterpret_cast<uintptr_t>(lse) & 3u) || (reinterpret_cast<uintptr_t>(kv_lens) & 3u) ||
+        (reinterpret_cast<uintptr_t>(q_lens) & 3u) || !aligned16(workspace))
         return FEDRAG_ERR_ALIAS;
     const size_t need = attn_workspace_bytes(shape->batch, shape->n_q_heads, shape->n_kv_heads, shape->d_head,
                                              shape->dtype, L_q, L_kv);
@@ -313,10 +315,30 @@ fedrag_status fedrag_partial_attn_quantized(const fedrag_shape* shape, int64_t L
     p.Q = Qs; p.K = K_codes; p.V = V_codes;
     p.K_params = K_params; p.V_params = V_params;
     p.quant_bits = bits;
+    p.kv_lens = kv_lens;
+    p.q_lens = q_lens;
     p.scale = softmax_scale;
     p.O = O_part; p.lse = lse;
     p.workspace = workspace; p.workspace_bytes = workspace_bytes;
     return dev(launch_partial_attn(p, (hipStream_t)stream));
+}
+
+fedrag_status fedrag_partial_attn_quantized(const fedrag_shape* shape, int64_t L_q, int64_t L_kv, const void* Qs,
+                                            const uint8_t* K_codes, const float* K_params, const uint8_t* V_codes,
+                                            const float* V_params, int32_t bits, float softmax_scale, float* O_part,
+                                            float* lse, void* workspace, size_t workspace_bytes, void* stream) {
+    return attn_on_codes(shape, L_q, L_kv, Qs, K_codes, K_params, V_codes, V_params, bits, nullptr, nullptr, false,
+                         softmax_scale, O_part, lse, workspace, workspace_bytes, stream);
+}
+
+fedrag_status fedrag_partial_attn_varlen_quantized(const fedrag_shape* shape, int64_t L_q, int64_t L_kv,
+                                                   const void* Qs, const uint8_t* K_codes, const float* K_params,
+                                                   const uint8_t* V_codes, const float* V_params, int32_t bits,
+                                                   const int32_t* kv_lens, const int32_t* q_lens, float softmax_scale,
+                                                   float* O_part, float* lse, void* workspace, size_t workspace_bytes,
+                                                   void* stream) {
+    return attn_on_codes(shape, L_q, L_kv, Qs, K_codes, K_params, V_codes, V_params, bits, kv_lens, q_lens, true,
+                         softmax_scale, O_part, lse, workspace, workspace_bytes, stream);
 }
 
 fedrag_status fedrag_local_attn(const fedrag_shape* shape, int64_t L_q, int64_t L_kv, const void* Q, const void* K,

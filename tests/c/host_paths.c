@@ -98,6 +98,12 @@ int main(void) {
     EXPECT(fedrag_partial_attn_quantized(&s, 1, 64, P(1), PU(2), PF(3), PU(4), PF(5), 5, sc, PF(6), PF(7), NULL, 0, NULL), FEDRAG_ERR_UNSUPPORTED);
     EXPECT(fedrag_partial_attn_quantized(&f32, 1, 64, P(1), PU(2), PF(3), PU(4), PF(5), 8, sc, PF(6), PF(7), NULL, 0, NULL), FEDRAG_ERR_UNSUPPORTED);
     EXPECT(fedrag_partial_attn_quantized(&s, 1, 64, P(1), PU(2), NULL, PU(4), PF(5), 8, sc, PF(6), PF(7), NULL, 0, NULL), FEDRAG_ERR_NULL);
+    EXPECT(fedrag_partial_attn_quantized(&s, 300, 64, P(1), PU(2), PF(3), PU(4), PF(5), 8, 0.0f, PF(6), PF(7), NULL, 0, NULL), FEDRAG_ERR_SHAPE);
+    EXPECT(fedrag_partial_attn_varlen_quantized(&s, 300, 64, P(1), PU(2), PF(3), PU(4), PF(5), 4, NULL, NULL, sc, PF(6), PF(7), NULL, 0, NULL), FEDRAG_ERR_NULL);
+    EXPECT(fedrag_partial_attn_varlen_quantized(&s, 300, 64, P(1), PU(2), PF(3), PU(4), PF(5), 6, PI(8), NULL, sc, PF(6), PF(7), NULL, 0, NULL), FEDRAG_ERR_UNSUPPORTED);
+    EXPECT(fedrag_partial_attn_varlen_quantized(&f32, 300, 64, P(1), PU(2), PF(3), PU(4), PF(5), 4, PI(8), NULL, sc, PF(6), PF(7), NULL, 0, NULL), FEDRAG_ERR_UNSUPPORTED);
+    EXPECT(fedrag_partial_attn_varlen_quantized(&s, 300, 64, P(1), PU(2), (float*)((char*)P(3) + 4), PU(4), PF(5), 4, PI(8), NULL, sc, PF(6), PF(7), NULL, 0, NULL), FEDRAG_ERR_ALIAS);
+    EXPECT(fedrag_partial_attn_varlen_quantized(&s, 0, 64, NULL, NULL, NULL, NULL, NULL, 4, NULL, NULL, sc, NULL, NULL, NULL, 0, NULL), FEDRAG_OK);
     {
         int64_t L[3] = {4096, 0, 4096}, Lneg[2] = {5, -1};
         const void* Ks[3] = {P(2), NULL, P(3)};

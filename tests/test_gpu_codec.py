@@ -177,8 +177,87 @@ def test_partial_attn_on_codes(oracle, case, bits):
     assert do <= 1e-3 and dl <= 1e-4
 
 
-def test_partial_attn_on_codes_rejects_other_shapes():
-    Q = torch.zeros((1, 8, 64, 128), dtype=torch.bfloat16, device=DEV)       # prefill shape
+PREFILL_Q_CASES = [
+    # name, B, Hq, Hkv, d, Lq, L, dtype                         the tiled kernel rebuilding key tiles from codes
+    ("rerank_d64", 2, 4, 4, 64, 300, 300, "bf16"),             # 2 query tiles, 5 key tiles, ragged
+    ("prefill_d128", 1, 8, 2, 128, 70, 500, "bf16"),           # d = 128, two chunks per thread and tile
+    ("prefill_d128_f16", 1, 4, 2, 128, 200, 333, "f16"),
+    ("kv_runs_d64", 1, 2, 1, 64, 40, 1500, "bf16"),            # few query tiles: keys cut into runs, partials merged
+    ("decode_shape_d64", 2, 8, 2, 64, 1, 700, "bf16"),         # decode shape with d = 64: also the tiled kernel
+]
+
+
+@pytest.mark.parametrize("bits", [8, 4])
+@pytest.mark.parametrize("case", PREFILL_Q_CASES, ids=[c[0] for c in PREFILL_Q_CASES])
+def test_partial_attn_on_codes_at_prefill_shapes(oracle, case, bits):
+    name, B, Hq, Hkv, d, Lq, L, dt = case
+    dtype = W.torch_dtype(dt)
+    seed = 900 + len(name) + bits
+    keys = W.make_keys(Hkv, d, Lq, L, 1, seed=seed, dtype=dtype)
+    rnd = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dtype)
+    mk = lambda H, n, tid: W.activations(B, H, n, d, seed=seed, tensor_id=tid, outliers=True, dtype=dtype)
+    Qs = rnd(oracle.scramble(mk(Hq, Lq, W.TID_Q), keys.phi_q, keys.perm_q))
+    Ks = rnd(oracle.scramble(mk(Hkv, L, W.TID_K), keys.phi_k, keys.perm_kv[0]))
+    Vs = rnd(oracle.scramble(mk(Hkv, L, W.TID_V), keys.phi_v, keys.perm_kv[0]))
+    kc, kp = oracle.quantize_rows(Ks, bits)
+    vc, vp = oracle.quantize_rows(Vs, bits)
+    t = lambda a: torch.from_numpy(a).to(DEV)
+    O, lse = fb.fedrag_partial_attn_quantized(Qs.to(DEV), t(kc), t(kp), t(vc), t(vp), bits)
+    Kh = torch.from_numpy(oracle.dequantize_rows(kc, kp, bits)).to(dtype)
+    Vh = torch.from_numpy(oracle.dequantize_rows(vc, vp, bits)).to(dtype)
+    Or, lr = oracle.partial_attn(Qs, Kh, Vh)
+    PT.check_attn(O, lse, Or, lr, dtype, f"{name}/{bits}", report=True)
+    # the same tiles rebuilt by the dequantise call and attended to by the 16-bit call: identical values in on-chip
+    # memory, identical arithmetic after that
+    Kd = fb.fedrag_dequantize_rows(t(kc), t(kp), bits, dtype)
+    Vd = fb.fedrag_dequantize_rows(t(vc), t(vp), bits, dtype)
+    O2, lse2 = fb.fedrag_partial_attn(Qs.to(DEV), Kd, Vd)
+    torch.cuda.synchronize()
+    if name != "decode_shape_d64":   # (that one compares two different kernels)
+        assert torch.equal(O, O2) and torch.equal(lse, lse2), "fused call differs from dequantise + attend"
+
+
+@pytest.mark.parametrize("bits", [8, 4])
+def test_reranker_batch_on_codes(oracle, bits):
+    """The re-ranker's padded batch (Section 5.2) with K', V' as codes (Section 7.5): per-sequence key and query
+    counts, padding poisoned in the codes AND in the parameters, padding query rows not written."""
+    dtype = torch.bfloat16
+    B, H, d, Lmax = 5, 4, 64, 400
+    lens = [400, 129, 0, 64, 333]
+    seed = 950 + bits
+    keys = W.make_keys(H, d, Lmax, Lmax, 1, seed=seed, dtype=dtype, permute_q=False)
+    rnd = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dtype)
+    mk = lambda tid: W.activations(B, H, Lmax, d, seed=seed, tensor_id=tid, outliers=True, dtype=dtype)
+    Qs = rnd(oracle.scramble(mk(W.TID_Q), keys.phi_q, None))
+    Ks = rnd(oracle.scramble(mk(W.TID_K), keys.phi_k, None))
+    Vs = rnd(oracle.scramble(mk(W.TID_V), keys.phi_v, None))
+    kc, kp = oracle.quantize_rows(Ks, bits)
+    vc, vp = oracle.quantize_rows(Vs, bits)
+    Kh = torch.from_numpy(oracle.dequantize_rows(kc, kp, bits)).to(dtype)
+    Vh = torch.from_numpy(oracle.dequantize_rows(vc, vp, bits)).to(dtype)
+    lens_t = torch.tensor(lens, dtype=torch.int32)
+    Or, lr = oracle.partial_attn_varlen(Qs, Kh, Vh, lens_t)
+    kc, kp, vc, vp = kc.copy(), kp.copy(), vc.copy(), vp.copy()
+    for b, n in enumerate(lens):   # poison: codes all ones, parameters NaN / Inf
+        kc[b, :, n:] = 255
+        vc[b, :, n:] = 255
+        kp[b, :, n:] = np.nan
+        vp[b, :, n:] = np.inf
+    t = lambda a: torch.from_numpy(a).to(DEV)
+    O = torch.full((B, H, Lmax, d), 7.0, dtype=torch.float32, device=DEV)
+    lse = torch.full((B, H, Lmax), 7.0, dtype=torch.float32, device=DEV)
+    fb.fedrag_partial_attn_varlen_quantized(Qs.to(DEV), t(kc), t(kp), t(vc), t(vp), bits, lens_t.to(DEV), O_part=O,
+                                            lse=lse, q_lens=lens_t.to(DEV))
+    torch.cuda.synchronize()
+    for b, n in enumerate(lens):
+        if n:
+            PT.check_attn(O[b:b + 1, :, :n], lse[b:b + 1, :, :n], Or[b:b + 1, :, :n], lr[b:b + 1, :, :n], dtype,
+                          f"pair {b} at {bits} bits", report=True)
+        assert bool((O[b, :, n:] == 7.0).all()) and bool((lse[b, :, n:] == 7.0).all()), "padding rows were written"
+
+
+def test_partial_attn_on_codes_rejects_fp32_storage():
+    Q = torch.zeros((1, 8, 64, 128), dtype=torch.float32, device=DEV)
     c = torch.zeros((1, 2, 64, 128), dtype=torch.uint8, device=DEV)
     p = torch.zeros((1, 2, 64, 2), dtype=torch.float32, device=DEV)
     with pytest.raises(fb.FedragError) as e:
