@@ -133,7 +133,7 @@ static bool use_decode_kernel(int Hq, int Hkv, int64_t Lq) { return (int64_t)(Hq
 // When those workgroups cover less than half of the compute units, the keys are cut into runs of at least
 // kPreMinTilesPerSplit tiles (so that a workgroup's fixed cost stays small beside its tiles) for one round of
 // workgroups over the chip; otherwise every shard is one run.
-KeyRuns attn_plan_runs(int B, int Hq, int Hkv, int dtype, int64_t Lq, int n, const int64_t* Ls) {
+KeyRuns attn_plan_runs(int B, int Hq, int Hkv, int dtype, int64_t Lq, int n, const int64_t* Ls, bool codes4) {
     KeyRuns r;
     for (int i = 0; i < kMaxShards; ++i) {
         r.K[i] = r.V[i] = nullptr;
@@ -147,7 +147,7 @@ KeyRuns attn_plan_runs(int B, int Hq, int Hkv, int dtype, int64_t Lq, int n, con
     int64_t total = 0;
     for (int i = 0; i < n; ++i) total += Ls[i] > 0 ? Ls[i] : 0;
     const bool decode = use_decode_kernel(Hq, Hkv, Lq);
-    const int64_t cus = FEDRAG_DEC_WGS;
+    const int64_t cus = (int64_t)FEDRAG_DEC_WGS * ((codes4 && decode) ? kDecCodesOcc : 1);
     int64_t per = INT64_MAX;  // keys per run before rebalancing inside a shard
     int64_t quantum = 1;
     if (dtype != FEDRAG_F32 && total > 0 && Lq > 0) {
@@ -191,7 +191,7 @@ KeyRuns attn_plan_runs(int B, int Hq, int Hkv, int dtype, int64_t Lq, int n, con
 
 KeyRuns attn_runs_of(const AttnProblem& p) {
     if (p.n_shards <= 1) {
-        KeyRuns r = attn_plan_runs(p.B, p.Hq, p.Hkv, p.dtype, p.Lq, 1, &p.Lkv);
+        KeyRuns r = attn_plan_runs(p.B, p.Hq, p.Hkv, p.dtype, p.Lq, 1, &p.Lkv, p.quant_bits == 4 && p.D == 128);
         r.K[0] = p.K;
         r.V[0] = p.V;
         if (p.single_run && r.n_runs > 1) {  // all keys of the shard in one run (a whole number of key tiles)
@@ -213,10 +213,15 @@ KeyRuns attn_runs_of(const AttnProblem& p) {
 bool attn_uses_decode_kernel(int Hq, int Hkv, int64_t Lq) { return use_decode_kernel(Hq, Hkv, Lq); }
 
 size_t attn_workspace_bytes(int B, int Hq, int Hkv, int D, int dtype, int64_t Lq, int n, const int64_t* Ls) {
-    const KeyRuns r = attn_plan_runs(B, Hq, Hkv, dtype, Lq, n, Ls);
-    if (r.n_runs <= 1) return 0;
+    // one size serves a call on 16-bit values and the same call on 4-bit transport codes (more, shorter runs)
+    int runs = attn_plan_runs(B, Hq, Hkv, dtype, Lq, n, Ls, false).n_runs;
+    if (n == 1 && D == 128 && dtype != FEDRAG_F32) {
+        const int on_codes = attn_plan_runs(B, Hq, Hkv, dtype, Lq, n, Ls, true).n_runs;
+        if (on_codes > runs) runs = on_codes;
+    }
+    if (runs <= 1) return 0;
     const size_t rows = (size_t)B * Hq * (size_t)Lq;
-    return (size_t)r.n_runs * rows * (size_t)(D + 1) * sizeof(float);
+    return (size_t)runs * rows * (size_t)(D + 1) * sizeof(float);
 }
 
 template <int D>

@@ -89,11 +89,15 @@ __device__ __forceinline__ typename T::vec8 dequant8(uint32_t w, u32x2_t prm) { 
     return dequant_codes<T>(q, prm);
 }
 
+// On codes the kernel is bound by its own instruction stream (rebuilding every element costs more than fetching
+// it).  At 4 bits it runs with one register tile set per wave and kDecCodesOcc workgroups per compute unit instead
+// of one workgroup with a ring of two: the other workgroup's waves fill the issue slots a wave leaves while it
+// waits (measured 61 -> 56 us per shard of the decode workload; at 8 bits the ring of two stayed ahead, 60 vs 62).
 #ifndef FEDRAG_DEC_NBUF_Q8
 #define FEDRAG_DEC_NBUF_Q8 2
 #endif
 #ifndef FEDRAG_DEC_NBUF_Q4
-#define FEDRAG_DEC_NBUF_Q4 2
+#define FEDRAG_DEC_NBUF_Q4 1
 #endif
 #ifndef FEDRAG_DEC_NBUF
 #define FEDRAG_DEC_NBUF 2   // register tile sets per wave
@@ -106,7 +110,7 @@ __device__ __forceinline__ typename T::vec8 dequant8(uint32_t w, u32x2_t prm) { 
 #endif
 
 template <class T, int D, int QB>
-__global__ __launch_bounds__(kDecThreads, FEDRAG_DEC_OCC) void decode_attn_kernel(const typename T::elem* __restrict__ Q,
+__global__ __launch_bounds__(kDecThreads, QB == 4 ? kDecCodesOcc : FEDRAG_DEC_OCC) void decode_attn_kernel(const typename T::elem* __restrict__ Q,
                                                                      const KeyRuns runs,
                                                                      const float* __restrict__ Kprm,
                                                                      const float* __restrict__ Vprm, int R,

@@ -91,8 +91,9 @@ struct KeyRuns {
     int first[kMaxShards + 1];
     int n_runs;
 };
-// Plans the runs for n shards of lengths Ls (n >= 1); pointers are left unset.
-KeyRuns attn_plan_runs(int B, int Hq, int Hkv, int dtype, int64_t Lq, int n, const int64_t* Ls);
+// Plans the runs for n shards of lengths Ls (n >= 1); pointers are left unset.  codes4: the streaming kernel will
+// read 4-bit transport codes (d = 128 decode shapes), where it wants kDecCodesOcc workgroups per compute unit.
+KeyRuns attn_plan_runs(int B, int Hq, int Hkv, int dtype, int64_t Lq, int n, const int64_t* Ls, bool codes4 = false);
 bool attn_uses_decode_kernel(int Hq, int Hkv, int64_t Lq);  // G * Lq <= 16: the HBM-bound streaming kernel
 // bytes of workspace the plan needs (0 when there is a single run)
 size_t attn_workspace_bytes(int B, int Hq, int Hkv, int D, int dtype, int64_t Lq, int n, const int64_t* Ls);
@@ -110,6 +111,10 @@ constexpr int kDecWaves = 4;
 constexpr int kDecThreads = kDecWaves * 64;
 constexpr int kDecTile = 32;                      // keys per wave step
 constexpr int kDecStride = kDecWaves * kDecTile;  // keys per workgroup step
+#ifndef FEDRAG_DECQ_OCC
+#define FEDRAG_DECQ_OCC 2
+#endif
+constexpr int kDecCodesOcc = FEDRAG_DECQ_OCC;     // workgroups per compute unit when the kernel reads 4-bit codes
 // prefill kernel geometry (shared by the split planner and the kernel)
 constexpr int kPreWaves = 8;
 constexpr int kPreQ = 32;                     // query rows per wave (one 32-wide MFMA column tile)

@@ -13,12 +13,16 @@
 
 namespace fedrag {
 
-constexpr int kScrWaves = 4;
-constexpr int kScrThreads = kScrWaves * kWave;
+// Two shapes of the tiled kernel.  Plain rows (QB = 0): 4 waves per workgroup, one per SIMD, Phi^T in 128 registers
+// per wave for the whole kernel - the wave does little besides moving rows, and memory time hides it.  Rows that
+// leave through the transport codec (QB = 8, 4): the codec's ~110 vector instructions per 8-element chunk need a
+// second wave per SIMD to hide behind the other wave's memory time, and two waves only fit when Phi^T stays in LDS
+// and its operands are read per tile (32 KiB of LDS reads per 8 KiB of rows: a few per cent of the LDS rate).
+constexpr int scr_waves(int qb) { return qb ? 8 : 4; }
 constexpr int kScrPad = 8;    // elements of row padding in LDS (16 bytes: keeps 16-byte alignment, breaks bank stride)
 constexpr int kScrRows = 32;  // rows per wave step (two 16-row MFMA column tiles)
 #ifndef FEDRAG_SCR_NBUF
-#define FEDRAG_SCR_NBUF 3     // register row-tile sets per wave (ring)
+#define FEDRAG_SCR_NBUF 3     // register row-tile sets per wave (ring); the codec shape uses 2
 #endif
 #ifndef FEDRAG_SCR_WGS
 #define FEDRAG_SCR_WGS 256    // workgroups to aim for over the whole launch (one per CU)
@@ -60,7 +64,7 @@ __device__ __forceinline__ float structured_entry(float s_in_k, int p_in_inv_k, 
 // QB = 0: rows leave in the storage type.  QB = 8 or 4: each narrowed row goes through the transport codec instead
 // (same arithmetic as quantize_rows_kernel on the stored row) and leaves as codes plus (scale, lo).
 template <class T, int D, bool ST, int QB>
-__global__ __launch_bounds__(kScrThreads, 1) void scramble_rows_kernel(ScrambleJob job0, ScrambleJob job1,
+__global__ __launch_bounds__(scr_waves(QB) * kWave, 1) void scramble_rows_kernel(ScrambleJob job0, ScrambleJob job1,
                                                                        const int32_t* __restrict__ perm,
                                                                        int64_t perm_batch_stride,  // 0 or L
                                                                        int B, int H, int G, int64_t L, int members,
@@ -74,13 +78,16 @@ __global__ __launch_bounds__(kScrThreads, 1) void scramble_rows_kernel(ScrambleJ
     constexpr int NI = kScrRows / RPI;     // wave-wide loads per 32-row tile
     constexpr int KS = D / 32;             // contraction steps
     constexpr int MT = D / 16;             // output-column tiles
-    constexpr int NBUF = FEDRAG_SCR_NBUF;
+    constexpr int kScrWaves = scr_waves(QB);
+    constexpr int kScrThreads = kScrWaves * kWave;
+    constexpr bool kScrPhiLds = QB != 0;
+    constexpr int NBUF = QB ? 2 : FEDRAG_SCR_NBUF;
     constexpr int kPhiElems = D * LDP;
     constexpr int kTileElems = kScrWaves * kScrRows * LDP;
-    constexpr int kLdsElems = kPhiElems > kTileElems ? kPhiElems : kTileElems;
+    constexpr int kLdsElems = kScrPhiLds ? kPhiElems + kTileElems : (kPhiElems > kTileElems ? kPhiElems : kTileElems);
 
-    // Phi^T staging and the per-wave row tiles share one buffer: Phi^T is only needed until every wave has
-    // copied its MFMA operands into registers.
+    // Phi^T staging and the per-wave row tiles share one buffer when the operands are copied into registers (Phi^T
+    // is then only needed until every wave has done so); with kScrPhiLds Phi^T stays and the row tiles follow it.
     __shared__ __attribute__((aligned(16))) elem lds[kLdsElems];
 
     const ScrambleJob job = blockIdx.y == 0 ? job0 : job1;
@@ -121,13 +128,16 @@ __global__ __launch_bounds__(kScrThreads, 1) void scramble_rows_kernel(ScrambleJ
     // Phi^T operands for the whole kernel: phi[mt][ks] = Phi^T[16 mt + lane%16][32 ks + 8 (lane/16) .. +8]
     const int lr = lane % 16;
     const int lq = lane / 16;
-    vec8 phi[MT][KS];
+    vec8 phi[kScrPhiLds ? 1 : MT][kScrPhiLds ? 1 : KS];
+    if constexpr (!kScrPhiLds) {
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
+        for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks)
-            phi[mt][ks] = *(const vec8*)(&lds[(mt * 16 + lr) * LDP + ks * 32 + lq * 8]);
-    __syncthreads();  // Phi^T is dead from here on; the buffer becomes the row tiles
+            for (int ks = 0; ks < KS; ++ks)
+                phi[mt][ks] = *(const vec8*)(&lds[(mt * 16 + lr) * LDP + ks * 32 + lq * 8]);
+        __syncthreads();  // Phi^T is dead from here on; the buffer becomes the row tiles
+    }
+    const elem* phi_lds = &lds[lr * LDP + lq * 8];  // kScrPhiLds: operand (mt, ks) at + mt * 16 * LDP + ks * 32
     // structured form: S2 and the Hadamard normalisation, for this lane's output columns 16 mt + 4 lq + r
     f32x4_t post[ST ? MT : 1];
     if (ST) {
@@ -139,7 +149,7 @@ __global__ __launch_bounds__(kScrThreads, 1) void scramble_rows_kernel(ScrambleJ
             for (int r = 0; r < 4; ++r) post[mt][r] = b[mt * 16 + lq * 4 + r] * norm;
     }
 
-    elem* my = lds + wave * (kScrRows * LDP);
+    elem* my = lds + (kScrPhiLds ? kPhiElems : 0) + wave * (kScrRows * LDP);
 
     const int ld_row = lane / CH;        // row within one wave-wide load
     const int ld_col = (lane % CH) * 8;  // element offset of this lane's 16 bytes
@@ -185,6 +195,11 @@ __global__ __launch_bounds__(kScrThreads, 1) void scramble_rows_kernel(ScrambleJ
         }
 #pragma unroll
         for (int half = 0; half < 2; ++half) {
+            // kScrPhiLds: an offset the compiler cannot see through (always 0), so that the Phi^T operand reads
+            // stay with the MFMAs that use them instead of being hoisted into 128 registers again
+            int phi_off = 0;
+            if constexpr (kScrPhiLds) pin_here(phi_off);
+            const elem* phi_t = phi_lds + phi_off;
             // X^T operands: column = row (16 half + lane%16) of the tile, contraction slice 32 ks + 8 (lane/16)
             vec8 xop[KS];
 #pragma unroll
@@ -196,7 +211,12 @@ __global__ __launch_bounds__(kScrThreads, 1) void scramble_rows_kernel(ScrambleJ
             for (int mt = 0; mt < MT; ++mt) {
                 acc[mt] = zero_vec<f32x4_t>();
 #pragma unroll
-                for (int ks = 0; ks < KS; ++ks) acc[mt] = T::mfma16(phi[mt][ks], xop[ks], acc[mt]);
+                for (int ks = 0; ks < KS; ++ks) {
+                    if constexpr (kScrPhiLds)
+                        acc[mt] = T::mfma16(*(const vec8*)(phi_t + mt * 16 * LDP + ks * 32), xop[ks], acc[mt]);
+                    else
+                        acc[mt] = T::mfma16(phi[mt][ks], xop[ks], acc[mt]);
+                }
             }
             // the 16 rows of this half are only read by the operand loads above (same wave, in order):
             // overwrite them with the narrowed results
@@ -232,18 +252,29 @@ __global__ __launch_bounds__(kScrThreads, 1) void scramble_rows_kernel(ScrambleJ
                 // x - lo >= 0, so the sum is >= 1/2: converting to unsigned truncates = floors, and only the upper
                 // clamp can act; a constant row (range 0) gets steps 0, hence code 0
                 const float steps = range > 0.0f ? (float)LEVELS / range : 0.0f;
+                // 8 bits: floor, then the conversion to a byte, which saturates at 255 (the upper clamp of the
+                // definition; the argument is >= 1/2, so there is no lower one) and packs the code into its place
                 uint32_t q[8];
+                u32x2_t w8;
+                w8[0] = w8[1] = 0u;
+                if (QB == 8) {
 #pragma unroll
-                for (int e = 0; e < 8; ++e)
-                    q[e] = (uint32_t)fminf(__builtin_fmaf(x[e] - lo, steps, 0.5f), (float)LEVELS);
+                    for (int e = 0; e < 8; ++e) {
+                        const uint32_t old = e < 4 ? w8[0] : w8[1];
+                        const uint32_t nw = __builtin_amdgcn_cvt_pk_u8_f32(__builtin_floorf(__builtin_fmaf(x[e] - lo, steps, 0.5f)), e % 4, old);
+                        if (e < 4) w8[0] = nw;
+                        else w8[1] = nw;
+                    }
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e)
+                        q[e] = (uint32_t)fminf(__builtin_fmaf(x[e] - lo, steps, 0.5f), (float)LEVELS);
+                }
                 if (j < L) {
                     const int64_t row = slab_off(i) / D + j;  // row index over the whole tensor
                     uint8_t* out = (uint8_t*)job.Y + row * (D * QB / 8);
                     if (QB == 8) {
-                        u32x2_t w;
-                        w[0] = q[0] | (q[1] << 8) | (q[2] << 16) | (q[3] << 24);
-                        w[1] = q[4] | (q[5] << 8) | (q[6] << 16) | (q[7] << 24);
-                        __builtin_nontemporal_store(w, (u32x2_t*)(out + (lane % CH) * 8));
+                        __builtin_nontemporal_store(w8, (u32x2_t*)(out + (lane % CH) * 8));
                     } else {
                         const uint32_t w = q[0] | (q[1] << 4) | (q[2] << 8) | (q[3] << 12) | (q[4] << 16) |
                                            (q[5] << 20) | (q[6] << 24) | (q[7] << 28);
@@ -640,7 +671,8 @@ static hipError_t launch_scramble16(const RowsJob& j, hipStream_t stream) {
                                j.perm_batch_stride, j.H, j.G, (int)j.L);
         return hipGetLastError();
     }
-    const int64_t rows_per_pass = kScrWaves * kScrRows;  // rows one workgroup covers per ring step
+    const int waves = scr_waves(j.quant_bits);
+    const int64_t rows_per_pass = (int64_t)waves * kScrRows;  // rows one workgroup covers per ring step
     const int64_t passes = (j.L + rows_per_pass - 1) / rows_per_pass;  // per [L, d] slab
     // about one workgroup per CU over the whole launch, split evenly over (job, head); never more members than a
     // slab has passes
@@ -655,7 +687,7 @@ static hipError_t launch_scramble16(const RowsJob& j, hipStream_t stream) {
     dim3 grid((unsigned)(j.H * members * b_groups), (unsigned)j.n_jobs);
     const ScrambleJob a = device_job(j, 0), b = device_job(j, 1);
 #define FEDRAG_SCR_LAUNCH(ST_, QB_)                                                                              \
-    hipLaunchKernelGGL((scramble_rows_kernel<T, D, ST_, QB_>), grid, dim3(kScrThreads), 0, stream, a, b, j.perm, \
+    hipLaunchKernelGGL((scramble_rows_kernel<T, D, ST_, QB_>), grid, dim3(waves * kWave), 0, stream, a, b, j.perm, \
                        j.perm_batch_stride, B, j.H, j.G, j.L, members, tiles_per_slab, b_groups)
     if (j.structured) {
         if (j.quant_bits == 8) FEDRAG_SCR_LAUNCH(true, 8);
