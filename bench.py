@@ -30,8 +30,8 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16 MFMA
 # with this file's own command line, and they go stale when the kernel changes (re-run the profile then).
 TRAFFIC_PROFILE = "profiles/bench_llama8b_decode_hbm_traffic.txt"
 MEASURED_TRAFFIC_BYTES = {
-    "scramble_kv": int((516.46 + 512.02) * 2**20),
-    "partial_attn": int((512.48 + 0.51) * 2**20),
+    "scramble_kv": int((516.48 + 512.03) * 2**20),
+    "partial_attn": int((512.57 + 0.51) * 2**20),
 }
 MIN_ITERS = 20   # timed iterations of every extra leg (medians are reported beside the means)
 
