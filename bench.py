@@ -618,12 +618,14 @@ def achievable_leg(torch, dev):
     lib.fedrag_probe_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
     lib.fedrag_probe_read.argtypes = [vp, ctypes.c_size_t, vp, vp]
     lib.fedrag_probe_mfma_bf16.argtypes = [vp, ctypes.c_int, vp]
+    lib.fedrag_probe_mfma_bf16_random.argtypes = [vp, ctypes.c_int, vp]
     lib.fedrag_probe_mfma_bf16_flop.argtypes = [ctypes.c_int]
     lib.fedrag_probe_mfma_bf16_flop.restype = ctypes.c_double
     n = 1 << 30
-    a = torch.empty(n, dtype=torch.uint8, device=dev)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(0xFED2A6)
+    a = torch.randint(0, 256, (n,), dtype=torch.uint8, device=dev, generator=gen)  # bytes that toggle, as real data do
     b = torch.empty_like(a)
-    a.fill_(1)
     sink = torch.zeros(4, dtype=torch.float32, device=dev)
     stream = lambda: vp(torch.cuda.current_stream().cuda_stream)
 
@@ -634,6 +636,7 @@ def achievable_leg(torch, dev):
     tr = measure(torch, lambda: chk(lib.fedrag_probe_read(a.data_ptr(), n, sink.data_ptr(), stream())), MIN_ITERS, 3)
     iters = 4096
     tm = measure(torch, lambda: chk(lib.fedrag_probe_mfma_bf16(sink.data_ptr(), iters, stream())), MIN_ITERS, 3)
+    tmr = measure(torch, lambda: chk(lib.fedrag_probe_mfma_bf16_random(sink.data_ptr(), iters, stream())), MIN_ITERS, 3)
     flop = float(lib.fedrag_probe_mfma_bf16_flop(iters))
     ok = bool(torch.equal(a, b))
     del a, b
@@ -641,9 +644,13 @@ def achievable_leg(torch, dev):
             "read_GB/s": round(1.0 * n / tr["med_us"] / 1e3, 1), "read_frac_of_hbm_peak": round(1.0 * n / tr["med_us"] / 1e3 / HBM_PEAK_GBS, 4),
             "mfma_bf16_TFLOP/s": round(flop / tm["med_us"] / 1e6, 1),
             "mfma_frac_of_peak": round(flop / tm["med_us"] / 1e6 / MFMA_BF16_PEAK_TFLOPS, 4),
+            "mfma_bf16_random_operands_TFLOP/s": round(flop / tmr["med_us"] / 1e6, 1),
+            "mfma_random_operands_frac_of_peak": round(flop / tmr["med_us"] / 1e6 / MFMA_BF16_PEAK_TFLOPS, 4),
             "copy_verified": ok,
-            "what": "medians of 20 launches: 1 GiB device copy (read + write bytes), 1 GiB streaming read, "
-                    "256 workgroups x 8 waves x 4096 x 8 independent 32x32x16 bf16 MFMAs on register operands"}
+            "what": "medians of 20 launches: 1 GiB device copy of random bytes (read + write bytes) and 1 GiB streaming "
+                    "read, one 256-thread workgroup per compute unit; 256 workgroups x 8 waves x 4096 x 8 independent "
+                    "32x32x16 bf16 MFMAs on register operands, first with the same two smooth operands for every MFMA, "
+                    "then with hashed bell-shaped operands per accumulator (the chip clocks lower when operand bits toggle)"}
 
 
 def cpu_leg(torch, W, g, n_shards):

@@ -12,7 +12,8 @@ typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
 
 constexpr int kCopyThreads = 256;
-constexpr int kCopyBlocks = 256 * 8;  // eight workgroups per compute unit
+constexpr int kCopyBlocks = 256;  // one workgroup per compute unit: more workgroups in flight measured slower (a
+                                  // 1 GiB copy: 6.1 TB/s with 256 workgroups, 4.2-5.6 TB/s with 512 to 8192)
 
 // dst[i] = src[i] over n 16-byte words, grid-stride, every load and store a full 1 KiB wave access, non-temporal
 __global__ __launch_bounds__(kCopyThreads) void copy_kernel(u32x4_t* __restrict__ dst, const u32x4_t* __restrict__ src,
@@ -54,20 +55,45 @@ constexpr int kMfmaThreads = 512;  // two waves per SIMD
 constexpr int kMfmaBlocks = 256;   // one workgroup per compute unit
 constexpr int kMfmaAcc = 8;        // independent accumulators per wave
 
+__device__ inline uint32_t mix32(uint32_t x) {
+    x ^= x >> 16;
+    x *= 0x7feb352du;
+    x ^= x >> 15;
+    x *= 0x846ca68bu;
+    x ^= x >> 16;
+    return x;
+}
+
+// roughly normal value in (-2, 2) from 32 hashed bits: the centred sum of its four bytes
+__device__ inline float bell(uint32_t h) {
+    return ((float)(h & 255u) + (float)((h >> 8) & 255u) + (float)((h >> 16) & 255u) + (float)(h >> 24) - 510.f) * (1.f / 128.f);
+}
+
 // iters x kMfmaAcc dense bf16 32x32x16 MFMAs per wave on register operands: the matrix pipe's issue rate with nothing
-// else going on
+// else going on.  RANDOM = false: every MFMA multiplies the same two smooth operands (few bits toggle from one
+// instruction to the next).  RANDOM = true: every accumulator has operands of its own, filled with hashed
+// bell-shaped values as activations are; the chip then runs at a lower clock under its power limit, and this is
+// the rate a kernel working on real data can be compared with.
+template <bool RANDOM>
 __global__ __launch_bounds__(kMfmaThreads) void mfma_kernel(float* __restrict__ sink, int iters) {
-    bf16x8_t a, b;
-    for (int j = 0; j < 8; ++j) {
-        a[j] = (__bf16)(0.001f * (float)(threadIdx.x % 64 + j));
-        b[j] = (__bf16)(0.002f * (float)(j + 1));
-    }
+    bf16x8_t a[kMfmaAcc], b[kMfmaAcc];
+    for (int k = 0; k < kMfmaAcc; ++k)
+        for (int j = 0; j < 8; ++j) {
+            if (RANDOM) {
+                const uint32_t h = mix32(threadIdx.x * 977u + blockIdx.x * 131u + k * 17u + j);
+                a[k][j] = (__bf16)bell(h);
+                b[k][j] = (__bf16)bell(mix32(h + 0x9e3779b9u));
+            } else {
+                a[k][j] = (__bf16)(0.001f * (float)(threadIdx.x % 64 + j));
+                b[k][j] = (__bf16)(0.002f * (float)(j + 1));
+            }
+        }
     f32x16_t c[kMfmaAcc];
     for (int k = 0; k < kMfmaAcc; ++k)
         for (int j = 0; j < 16; ++j) c[k][j] = 0.f;
     for (int it = 0; it < iters; ++it) {
 #pragma unroll
-        for (int k = 0; k < kMfmaAcc; ++k) c[k] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c[k], 0, 0, 0);
+        for (int k = 0; k < kMfmaAcc; ++k) c[k] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[k], b[k], c[k], 0, 0, 0);
     }
     float s = 0.f;
     for (int k = 0; k < kMfmaAcc; ++k)
@@ -101,10 +127,18 @@ double fedrag_probe_mfma_bf16_flop(int iters) {
     return (double)kMfmaBlocks * (kMfmaThreads / 64) * (double)iters * kMfmaAcc * (2.0 * 32 * 32 * 16);
 }
 
-// The bare MFMA loop; sink: one device float (left untouched in practice).  1 <= iters <= 1 << 20.
+// The bare MFMA loop on two smooth operands; sink: one device float (left untouched in practice).
+// 1 <= iters <= 1 << 20.
 int fedrag_probe_mfma_bf16(float* sink, int iters, void* stream) {
     if (!sink || iters < 1 || iters > (1 << 20)) return 1;
-    hipLaunchKernelGGL(mfma_kernel, dim3(kMfmaBlocks), dim3(kMfmaThreads), 0, (hipStream_t)stream, sink, iters);
+    hipLaunchKernelGGL(mfma_kernel<false>, dim3(kMfmaBlocks), dim3(kMfmaThreads), 0, (hipStream_t)stream, sink, iters);
+    return hipGetLastError() == hipSuccess ? 0 : 2;
+}
+
+// The same loop with hashed, bell-shaped operand values, different for every accumulator (same flop count).
+int fedrag_probe_mfma_bf16_random(float* sink, int iters, void* stream) {
+    if (!sink || iters < 1 || iters > (1 << 20)) return 1;
+    hipLaunchKernelGGL(mfma_kernel<true>, dim3(kMfmaBlocks), dim3(kMfmaThreads), 0, (hipStream_t)stream, sink, iters);
     return hipGetLastError() == hipSuccess ? 0 : 2;
 }
 
