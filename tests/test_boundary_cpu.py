@@ -461,3 +461,29 @@ def test_calls_without_rows_accept_null_tensors(lib):
     # with rows the same pointers are refused
     assert lib.fedrag_scramble_q(ctypes.byref(s), 1, None, None, None, None, None) == fb.ERR_NULL
     assert lib.fedrag_unscramble(ctypes.byref(s), 1, None, None, None, None, None) == fb.ERR_NULL
+
+
+def test_probe_library_exports_and_refuses_bad_arguments():
+    """The rate probes bench.py reports as `achievable` live in a library of their own; without a device only the
+    host-side argument checks can run (a refused call launches nothing)."""
+    if not os.path.exists(fbuild.PROBES_LIB):
+        fbuild.build_probes(force=True)
+    p = ctypes.CDLL(fbuild.PROBES_LIB)
+    for name in ("fedrag_probe_copy", "fedrag_probe_read", "fedrag_probe_mfma_bf16", "fedrag_probe_mfma_bf16_random",
+                 "fedrag_probe_mfma_bf16_flop"):
+        assert hasattr(p, name), name
+    vp = ctypes.c_void_p
+    p.fedrag_probe_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
+    p.fedrag_probe_read.argtypes = [vp, ctypes.c_size_t, vp, vp]
+    p.fedrag_probe_mfma_bf16.argtypes = [vp, ctypes.c_int, vp]
+    p.fedrag_probe_mfma_bf16_random.argtypes = [vp, ctypes.c_int, vp]
+    p.fedrag_probe_mfma_bf16_flop.argtypes = [ctypes.c_int]
+    p.fedrag_probe_mfma_bf16_flop.restype = ctypes.c_double
+    assert p.fedrag_probe_copy(None, None, 1024, None) == 1
+    assert p.fedrag_probe_copy(vp(0x1000), vp(0x2000), 1000, None) == 1      # not a multiple of 16
+    assert p.fedrag_probe_copy(vp(0x1008), vp(0x2000), 1024, None) == 1      # misaligned
+    assert p.fedrag_probe_read(None, 1024, vp(0x1000), None) == 1
+    assert p.fedrag_probe_mfma_bf16(None, 16, None) == 1
+    assert p.fedrag_probe_mfma_bf16_random(vp(0x1000), 0, None) == 1
+    # 256 workgroups x 8 waves x iters x 8 MFMAs of 2 * 32 * 32 * 16 flop
+    assert p.fedrag_probe_mfma_bf16_flop(3) == 256 * 8 * 3 * 8 * 2.0 * 32 * 32 * 16
