@@ -1,9 +1,9 @@
 // Prefill-shaped partial attention (Section 4.1, per-node local computation) for 16-bit storage: many query rows
-// per head against one KV shard.  Bound by the matrix pipe at the clock the chip sustains on real operand data
-// together with the LDS operand reads that feed it (1 KiB per MFMA at 32 query rows per wave); the softmax's vector
-// work comes third.  Vector instructions overlap matrix instructions best inside one wave (in the shadow of that
-// wave's own MFMAs), so each wave software-pipelines across key tiles: in iteration t it computes
-// S^T(t) = K'(t) Q'^T and then issues the MFMAs of O^T += V'(t-1)^T P(t-1)^T together with the online softmax of tile t.
+// per head against one KV shard.  Bound by the matrix pipe at the clock the chip sustains on real operand data plus
+// the part of the softmax's vector work that does not overlap it.  Vector instructions overlap matrix instructions
+// best inside one wave (in the shadow of that wave's own MFMAs), so each wave software-pipelines across key tiles:
+// in iteration t it computes S^T(t) = K'(t) Q'^T and then issues the MFMAs of O^T += V'(t-1)^T P(t-1)^T together with
+// the online softmax of tile t.
 //   * one workgroup = 8 waves x 32 query rows = 256 query rows of one (sequence, query head);
 //   * K'/V' tiles of 64 keys are shared by the 8 waves through LDS (two slots each), filled by LDS-direct global
 //     loads one iteration ahead (no staging registers), one workgroup barrier per iteration;
