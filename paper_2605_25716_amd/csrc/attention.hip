@@ -272,10 +272,12 @@ hipError_t launch_partial_attn(const AttnProblem& p_in, hipStream_t stream) {
         if (total == 0) return launch_fill_empty(p.O, p.lse, rows, p.D, stream);
         const bool decode = use_decode_kernel(p.Hq, p.Hkv, p.Lq);
         bool one_launch_per_shard = p.dtype == FEDRAG_F32;  // the accuracy path has no run table
-        if (!one_launch_per_shard && !decode) {
-            // prefill kernel with the chip already covered by query tiles (every shard one run): a launch per shard
-            // keeps the workgroups of a launch on one shard's K', V' (8 shards of 8192 keys, 4096 x 64 query rows:
-            // 8.2 ms against 8.9 ms with all shards in one launch); the partials and their aggregation are the same
+        if (!one_launch_per_shard && (!decode || (int64_t)p.B * p.Hkv >= decode_target_wgs())) {
+            // The chip is already covered by one shard's workgroups (prefill: query tiles; decode: as many
+            // (sequence, KV head) units as compute units) and every shard is one run: a launch per shard keeps the
+            // workgroups of a launch on one shard's K', V' (prefill, 8 shards of 8192 keys, 4096 x 64 query rows:
+            // 8.2 ms against 8.9 ms with all shards in one launch; decode, 8 shards of 8 GiB: 9.55 against 10.05 ms);
+            // the partials and their aggregation are the same
             const KeyRuns plan = attn_runs_of(p);
             one_launch_per_shard = true;
             for (int i = 0; i < p.n_shards; ++i)
