@@ -132,9 +132,11 @@ fedrag_status fedrag_partial_attn_static(const fedrag_shape* shape, int64_t L_q,
 /*
  * Section 4.1 as a whole on a Compute Node that holds the shards of several Context Owners for the same queries:
  * the per-shard computation of fedrag_partial_attn on each of the n_shards shards and the aggregation of
- * fedrag_lse_merge over them, in one call (one attention launch over all shards' keys plus one aggregation launch,
- * instead of one of each per shard - what counts when a shard is a few thousand tokens and a launch costs as much
- * as its work).  The result equals attention over the concatenation of the shards' keys (eq. (1)).
+ * fedrag_lse_merge over them, in one call.  Small problems take one attention launch over all shards' keys plus one
+ * aggregation launch, instead of one of each per shard (what counts when a shard is a few thousand tokens and a
+ * launch costs as much as its work); when a single shard's work already covers the chip the attention is launched
+ * shard by shard and aggregated once.  The result equals attention over the concatenation of the shards' keys
+ * (eq. (1)).
  * n_shards : 1 .. FEDRAG_MAX_SHARDS.  L_kv, Ks, Vs : HOST arrays of n_shards entries - shard lengths (>= 0; an empty
  * shard contributes nothing and its pointers may be NULL) and DEVICE pointers to [B,Hkv,L_kv[i],d] tensors in
  * shape->dtype (16-byte aligned).  The arrays are read during the call only.
