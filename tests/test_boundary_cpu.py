@@ -487,3 +487,28 @@ def test_probe_library_exports_and_refuses_bad_arguments():
     assert p.fedrag_probe_mfma_bf16_random(vp(0x1000), 0, None) == 1
     # 256 workgroups x 8 waves x iters x 8 MFMAs of 2 * 32 * 32 * 16 flop
     assert p.fedrag_probe_mfma_bf16_flop(3) == 256 * 8 * 3 * 8 * 2.0 * 32 * 32 * 16
+
+
+def test_bench_means_leave_out_stalls():
+    """bench.py's per-call mean: a sample beyond three medians (a stall of the host or the box between the two event
+    records) is left out and counted; the median is taken over everything."""
+    import importlib.util
+    spec = importlib.util.spec_from_file_location("bench_module", os.path.join(ROOT, "bench.py"))
+    bench = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(bench)
+
+    class Ev:
+        def __init__(self, t):
+            self.t = t
+
+        def elapsed_time(self, other):
+            return other.t - self.t
+
+    timer = bench.CallTimer(torch=None)
+    ms = [0.086] * 19 + [25.0]            # 19 calls of 86 us and one that spans a 25 ms stall
+    timer.pairs["partial_attn"] = [(Ev(0.0), Ev(x)) for x in ms]
+    timer.pairs["clean"] = [(Ev(0.0), Ev(0.190 + 0.001 * (i % 3))) for i in range(20)]
+    s = timer.summary()
+    assert s["partial_attn"]["stalls_left_out"] == 1 and abs(s["partial_attn"]["avg_us"] - 86.0) < 1e-6
+    assert abs(s["partial_attn"]["med_us"] - 86.0) < 1e-6 and abs(s["partial_attn"]["max_us"] - 25000.0) < 1e-6
+    assert s["clean"]["stalls_left_out"] == 0 and 190.0 <= s["clean"]["avg_us"] <= 192.0
